@@ -1,0 +1,12 @@
+"""MI355X-native gradient-aggregation path of DeAR (decoupled all-reduce with tensor fusion).
+
+The product is libdear.so (C ABI in include/dear.h, HIP kernels for gfx950); this package
+is its thin ctypes binding.  Importing the package does not load the library; the first
+call does, and raises if the library has not been built.
+"""
+from .binding import (  # noqa: F401
+    DEAR_BF16, DEAR_F32, DEAR_NO_LIMIT, DEAR_SHARD_ALIGN, Context, DearError, Plan,
+    dear_all_gather, dear_ctx_create, dear_plan, dear_plan_fixed_layers, dear_plan_tiles,
+    dear_reduce_scatter,
+    dear_scatter_params, dear_shard_update, dear_version, load_library, strerror,
+)

@@ -1,0 +1,118 @@
+"""Device-memory plumbing for the one-GPU emulation of P data-parallel workers.
+
+Allocates, with torch, what a caller of libdear owns: P replicas of per-layer gradient
+and parameter tensors and the three shard buffers, and binds them to a context.  Every
+step of the path itself runs in the library's kernels; nothing here computes.
+"""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence
+
+import torch
+
+from . import binding as B
+
+
+def _stream_handle(stream: Optional["torch.cuda.Stream"]) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return s.cuda_stream
+
+
+class EmulatedWorkers:
+    """P workers' tensors on one GPU plus a libdear context over them.
+
+    layout "flat": each replica is one allocation, layers start on 256-byte boundaries.
+    layout "separate": every layer tensor of every replica is its own allocation.
+    """
+
+    LAYER_ALIGN_BYTES = 256
+
+    def __init__(self, sizes: Sequence[int], P: int, grad_dtype: str, threshold_bytes: int,
+                 device: str = "cuda:0", layout: str = "flat", plan: Optional[B.Plan] = None):
+        if not torch.cuda.is_available():
+            raise RuntimeError("EmulatedWorkers needs a GPU; there is no CPU path")
+        B.load_library()
+        self.sizes = list(sizes)
+        self.P = P
+        self.grad_dtype = grad_dtype
+        self.device = torch.device(device)
+        tg = torch.float32 if grad_dtype == "f32" else torch.bfloat16
+        g = 4 if grad_dtype == "f32" else 2
+        self.plan = plan if plan is not None else B.dear_plan(self.sizes, P, threshold_bytes, g)
+        if self.plan.grad_elem_bytes != g or self.plan.P != P or self.plan.layer_sizes != self.sizes:
+            raise ValueError("plan does not match the workers")
+
+        self.grads: List[List[torch.Tensor]] = []
+        self.params: List[List[torch.Tensor]] = []
+        self._keep = []
+        for _ in range(P):
+            self.grads.append(self._alloc_layers(tg, g, layout))
+            self.params.append(self._alloc_layers(torch.float32, 4, layout))
+
+        row = self.plan.total_shard_len
+        self.shard_grad = torch.zeros(P, row, dtype=torch.float32, device=self.device)
+        self.shard_param = torch.zeros(P, row, dtype=torch.float32, device=self.device)
+        self.shard_mom = torch.zeros(P, row, dtype=torch.float32, device=self.device)
+
+        gp = [t.data_ptr() for rep in self.grads for t in rep]
+        wp = [t.data_ptr() for rep in self.params for t in rep]
+        with torch.cuda.device(self.device):
+            self.ctx = B.dear_ctx_create(self.plan, B.DEAR_F32 if g == 4 else B.DEAR_BF16, gp, wp)
+
+    def _alloc_layers(self, dtype, elem_bytes: int, layout: str) -> List[torch.Tensor]:
+        if layout == "separate":
+            return [torch.zeros(n, dtype=dtype, device=self.device) for n in self.sizes]
+        if layout != "flat":
+            raise ValueError(layout)
+        a = self.LAYER_ALIGN_BYTES // elem_bytes
+        starts, pos = [], 0
+        for n in self.sizes:
+            starts.append(pos)
+            pos = (pos + n + a - 1) // a * a
+        buf = torch.zeros(max(pos, 1), dtype=dtype, device=self.device)
+        self._keep.append(buf)
+        return [buf[s:s + n] for s, n in zip(starts, self.sizes)]
+
+    # ------------------------------------------------------------------ data movement (plumbing)
+    def load_dense(self, dst_layers: List[torch.Tensor], dense: torch.Tensor) -> None:
+        """Copy a dense concatenation of all layers into one replica's layer tensors."""
+        pos = 0
+        for t in dst_layers:
+            t.copy_(dense[pos:pos + t.numel()])
+            pos += t.numel()
+
+    def dense(self, layers: List[torch.Tensor]) -> torch.Tensor:
+        return torch.cat([t.reshape(-1) for t in layers])
+
+    # ------------------------------------------------------------------ the path
+    def scatter_params(self, worker: int = 0, stream=None) -> None:
+        B.dear_scatter_params(self.ctx, worker, self.shard_param.data_ptr(), _stream_handle(stream))
+
+    def reduce_scatter(self, bucket: int = -1, stream=None) -> None:
+        B.dear_reduce_scatter(self.ctx, bucket, self.shard_grad.data_ptr(), _stream_handle(stream))
+
+    def shard_update(self, bucket: int, lr: float, momentum: float, stream=None) -> None:
+        B.dear_shard_update(self.ctx, bucket, self.shard_grad.data_ptr(), self.shard_param.data_ptr(),
+                            self.shard_mom.data_ptr(), lr, momentum, _stream_handle(stream))
+
+    def all_gather(self, bucket: int = -1, stream=None) -> None:
+        B.dear_all_gather(self.ctx, bucket, self.shard_param.data_ptr(), _stream_handle(stream))
+
+    def iteration(self, lr: float, momentum: float, per_bucket: bool = True, stream=None) -> None:
+        """One pass of the whole path on one stream: reduce-scatter the buckets in the order
+        their gradients become ready, update the owned shards, all-gather in forward order."""
+        nb = self.plan.n_buckets
+        if per_bucket:
+            for b in range(nb):
+                self.reduce_scatter(b, stream)
+            for b in range(nb):
+                self.shard_update(b, lr, momentum, stream)
+            for b in reversed(range(nb)):
+                self.all_gather(b, stream)
+        else:
+            self.reduce_scatter(-1, stream)
+            self.shard_update(-1, lr, momentum, stream)
+            self.all_gather(-1, stream)
+
+    def close(self) -> None:
+        self.ctx.destroy()
