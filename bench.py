@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the DeAR gradient-aggregation path on one MI355X.
+
+One step = one pass of the whole hot path over every bucket of the workload:
+reduce-scatter (pack fused) of all buckets in gradient-ready order, fused SGD-momentum
+update of the owned shards, all-gather (unpack fused) in forward order -- one launch
+per bucket and phase, back to back on one stream, inputs resident in HBM.
+
+Prints ONE JSON line.  `value` is effective GB/s = algorithmic bytes / wall time, with
+algorithmic bytes per step N*(g*P + 4*P + 28): reduce-scatter reads g*P*N and writes 4N,
+the update reads 12N and writes 8N, the all-gather reads 4N and writes 4*P*N.
+
+Extra objects on the line:
+  roofline      the phase that takes the most time, its algorithmic bytes per launch over
+                its average launch duration (HIP events on the launch stream), against
+                the 8 TB/s HBM peak
+  cpu_baseline  the CPU oracle timed on this host on a bounded sample of the same
+                workload (a baseline, not a target); its output is also compared with
+                the GPU's on that sample
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import torch
+
+import workloads as W
+
+HBM_PEAK_GBPS = 8000.0
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs (see profiles/); filled in per workload once measured, else null.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="bert_large", choices=W.WORKLOAD_NAMES)
+    ap.add_argument("--launch", default="per_bucket", choices=["per_bucket", "all_buckets"],
+                    help="one launch per bucket and phase (the DeAR schedule) or one per phase")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sample-buckets", type=int, default=2,
+                    help="buckets (from bucket 0) the CPU oracle is timed on")
+    return ap.parse_args()
+
+
+def fill_inputs(em, w, device):
+    param = W.make_flat_param(w, device)
+    for p in range(w.P):
+        em.load_dense(em.params[p], param)
+        em.load_dense(em.grads[p], W.make_flat_grad(w, p, 0, device))
+    del param
+    em.scatter_params(0)
+    torch.cuda.synchronize()
+
+
+def cpu_baseline_and_check(em, w, n_buckets):
+    """Time the oracle (single thread, as it stands) on the first n_buckets buckets of the
+    workload and compare the GPU's first iteration with it there."""
+    import numpy as np
+    import oracle
+
+    op = oracle.plan(w.sizes, w.P, w.threshold_bytes, w.grad_elem_bytes)
+    buckets = list(range(min(n_buckets, op.n_buckets)))
+    layers = [l for b in buckets
+              for l in range(int(op.bucket_first_layer[b]), int(op.bucket_first_layer[b]) + int(op.bucket_n_layers[b]))]
+
+    def host(t):
+        t = t.cpu().contiguous()
+        return t.view(torch.int16).numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.numpy()
+
+    grads = [[None] * w.n_layers for _ in range(w.P)]
+    params = [[None] * w.n_layers for _ in range(w.P)]
+    for p in range(w.P):
+        for l in layers:
+            grads[p][l] = host(em.grads[p][l])
+            params[p][l] = host(em.params[p][l]).copy()
+    row = op.total_shard_len
+    sg = np.zeros((w.P, row), np.float32)
+    sp = np.zeros_like(sg)
+    sm = np.zeros_like(sg)
+    for b in buckets:
+        oracle.scatter_params(op, params, 0, sp, bucket=b)
+
+    n_sample = int(sum(op.bucket_len[b] for b in buckets))
+    t0 = time.perf_counter()
+    for b in buckets:
+        oracle.reduce_scatter(op, b, grads, sg)
+    for b in buckets:
+        oracle.shard_update(op, b, sg, sp, sm, w.lr, w.momentum)
+    for b in reversed(buckets):
+        oracle.all_gather(op, b, sp, params)
+    dt = time.perf_counter() - t0
+    sample_bytes = n_sample * (w.grad_elem_bytes * w.P + 4 * w.P + 28)
+
+    # GPU: first iteration from the same state, then compare on the sample
+    em.iteration(w.lr, w.momentum, per_bucket=True)
+    torch.cuda.synchronize()
+    ok = True
+    for b in buckets:
+        lo, S = int(op.bucket_shard_base[b]), int(op.bucket_shard_len[b])
+        for dev, ref in ((em.shard_grad, sg), (em.shard_param, sp), (em.shard_mom, sm)):
+            got = dev[:, lo:lo + S].cpu().numpy()
+            ok = ok and np.array_equal(got.view(np.uint32), ref[:, lo:lo + S].view(np.uint32))
+    for p in (0, w.P - 1):
+        for l in layers:
+            ok = ok and np.array_equal(host(em.params[p][l]).view(np.uint32), params[p][l].view(np.uint32))
+    return {
+        "value": round(sample_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "sample": "buckets %s of %s (%d of %d elements, all %d workers), one iteration, %.1f s" % (
+            buckets, w.name, n_sample, w.N, w.P, dt),
+        "gpu_matches_oracle_on_sample": bool(ok),
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU's share of the path; runs on more than one GPU are "
+              "not part of this build (--gpus %d refused)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (there is no CPU path)", file=sys.stderr)
+        sys.exit(2)
+
+    from paper_2302_12445_amd.emulation import EmulatedWorkers
+
+    device = "cuda:0"
+    torch.cuda.set_device(0)
+    w = W.get_workload(args.workload)
+    em = EmulatedWorkers(w.sizes, w.P, w.grad_dtype, w.threshold_bytes, device)
+    fill_inputs(em, w, device)
+    nb = em.plan.n_buckets
+    per_bucket = args.launch == "per_bucket"
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline_and_check(em, w, args.sample_buckets)
+
+    for _ in range(args.warmup):
+        em.iteration(w.lr, w.momentum, per_bucket=per_bucket)
+    torch.cuda.synchronize()
+
+    # timed region: K steps; phase boundaries marked with events on the launch stream
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        ev[k][0].record()
+        if per_bucket:
+            for b in range(nb):
+                em.reduce_scatter(b)
+            ev[k][1].record()
+            for b in range(nb):
+                em.shard_update(b, w.lr, w.momentum)
+            ev[k][2].record()
+            for b in reversed(range(nb)):
+                em.all_gather(b)
+        else:
+            em.reduce_scatter(-1)
+            ev[k][1].record()
+            em.shard_update(-1, w.lr, w.momentum)
+            ev[k][2].record()
+            em.all_gather(-1)
+        ev[k][3].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    bytes_ = w.algorithmic_bytes()
+    ms_per_step = wall * 1e3 / args.steps
+    value = bytes_["total"] / (wall / args.steps) / 1e9
+    launches = nb if per_bucket else 1
+    phase_ms = {}
+    for i, name in enumerate(("rs", "update", "ag")):
+        phase_ms[name] = sum(ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(args.steps)) / args.steps
+    kernel_of = {"rs": "reduce_scatter_kernel", "update": "shard_update_kernel", "ag": "all_gather_kernel"}
+    dom = max(phase_ms, key=phase_ms.get)
+    achieved = bytes_[dom] / (phase_ms[dom] * 1e-3) / 1e9
+    roofline = {
+        "bound": "hbm", "kernel": kernel_of[dom], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+        "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
+        "bytes_per_launch": bytes_[dom] // launches, "launches_per_step": launches,
+        "avg_launch_ms": round(phase_ms[dom] / launches, 4),
+        "phases": {n: {"ms": round(phase_ms[n], 4), "GBps": round(bytes_[n] / (phase_ms[n] * 1e-3) / 1e9, 1)}
+                   for n in phase_ms},
+    }
+    line = {
+        "metric": "effective aggregation GB/s (RS+update+AG)", "value": round(value, 1), "unit": "GB/s",
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "P": w.P, "N": w.N, "n_layers": w.n_layers, "buckets": nb,
+                   "threshold_bytes": w.threshold_bytes if w.threshold_bytes != W.NO_LIMIT else "no limit",
+                   "grad_dtype": w.grad_dtype, "launch": args.launch,
+                   "algorithmic_bytes_per_step": bytes_["total"]},
+        "roofline": roofline,
+    }
+    if cpu is not None:
+        line["cpu_baseline"] = cpu
+    print(json.dumps(line), flush=True)
+    em.close()
+
+
+if __name__ == "__main__":
+    main()

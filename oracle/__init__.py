@@ -98,13 +98,25 @@ def plan(sizes: Sequence[int], P: int, threshold_bytes: int, grad_elem_bytes: in
                       bf[:B].copy(), bn[:B].copy(), bl[:B].copy(), bs[:B].copy(), bb[:B].copy())
 
 
-def _ptr_table(arrays: Sequence[Sequence[np.ndarray]], P: int, L: int):
+def _bucket_layers(pl: OraclePlan, buckets: Sequence[int]) -> List[int]:
+    out: List[int] = []
+    for b in buckets:
+        first = int(pl.bucket_first_layer[b])
+        out.extend(range(first, first + int(pl.bucket_n_layers[b])))
+    return out
+
+
+def _ptr_table(pl: OraclePlan, arrays: Sequence[Sequence[Optional[np.ndarray]]], layers: Sequence[int],
+               dtype, workers: Optional[range] = None):
+    """Host pointer table [p*L + l].  Only the listed layers (and workers) are needed by the
+    call; arrays of other layers may be None and get a null entry."""
+    P, L = pl.P, pl.L
     tab = (C.c_void_p * (P * L))()
-    for p in range(P):
+    for p in (range(P) if workers is None else workers):
         assert len(arrays[p]) == L
-        for l in range(L):
+        for l in layers:
             a = arrays[p][l]
-            assert a.flags["C_CONTIGUOUS"]
+            assert a is not None and a.dtype == dtype and a.size == pl.sizes[l] and a.flags["C_CONTIGUOUS"]
             tab[p * L + l] = a.ctypes.data
     return tab
 
@@ -133,12 +145,10 @@ def reduce_scatter(pl: OraclePlan, bucket: int, grads: Sequence[Sequence[np.ndar
     lib = _load()
     stride = _check_rows(pl, shard_grad)
     want = np.float32 if pl.grad_elem_bytes == 4 else np.uint16
-    for p in range(pl.P):
-        for l in range(pl.L):
-            assert grads[p][l].dtype == want and grads[p][l].size == pl.sizes[l]
-    tab = _ptr_table(grads, pl.P, pl.L)
+    todo = _buckets(pl, bucket, forward=False)
+    tab = _ptr_table(pl, grads, _bucket_layers(pl, todo), want)
     s0, s1 = (0, pl.P) if shards is None else (shards.start, shards.stop)
-    for b in _buckets(pl, bucket, forward=False):
+    for b in todo:
         lib.oracle_reduce_scatter(
             _p(pl.sizes, C.c_int64), C.c_int32(pl.L), C.c_int32(pl.P), C.c_int32(pl.grad_elem_bytes),
             _p(pl.layer_offset, C.c_int64),
@@ -167,12 +177,10 @@ def all_gather(pl: OraclePlan, bucket: int, shard_param: np.ndarray,
     """params[p][l]: worker p's parameter tensor of layer l (float32), overwritten."""
     lib = _load()
     stride = _check_rows(pl, shard_param)
-    for p in range(pl.P):
-        for l in range(pl.L):
-            assert params[p][l].dtype == np.float32 and params[p][l].size == pl.sizes[l]
-    tab = _ptr_table(params, pl.P, pl.L)
+    todo = _buckets(pl, bucket, forward=True)
     p0, p1 = (0, pl.P) if workers is None else (workers.start, workers.stop)
-    for b in _buckets(pl, bucket, forward=True):
+    tab = _ptr_table(pl, params, _bucket_layers(pl, todo), np.float32, range(p0, p1))
+    for b in todo:
         lib.oracle_all_gather(
             _p(pl.sizes, C.c_int64), C.c_int32(pl.L), C.c_int32(pl.P), _p(pl.layer_offset, C.c_int64),
             C.c_int32(int(pl.bucket_first_layer[b])), C.c_int32(int(pl.bucket_n_layers[b])),
@@ -181,12 +189,13 @@ def all_gather(pl: OraclePlan, bucket: int, shard_param: np.ndarray,
 
 
 def scatter_params(pl: OraclePlan, params: Sequence[Sequence[np.ndarray]], worker: int,
-                   shard_param: np.ndarray) -> None:
-    """Seed every bucket's parameter shards from worker `worker`'s full tensors."""
+                   shard_param: np.ndarray, bucket: int = -1) -> None:
+    """Seed the parameter shards (every bucket, or one) from worker `worker`'s full tensors."""
     lib = _load()
     stride = _check_rows(pl, shard_param)
-    tab = _ptr_table(params, pl.P, pl.L)
-    for b in range(pl.n_buckets):
+    todo = _buckets(pl, bucket, forward=False)
+    tab = _ptr_table(pl, params, _bucket_layers(pl, todo), np.float32, range(worker, worker + 1))
+    for b in todo:
         lib.oracle_scatter_params(
             _p(pl.sizes, C.c_int64), C.c_int32(pl.L), C.c_int32(pl.P), _p(pl.layer_offset, C.c_int64),
             C.c_int32(int(pl.bucket_first_layer[b])), C.c_int32(int(pl.bucket_n_layers[b])),

@@ -63,6 +63,10 @@ def load_library() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError("libdear.so is not built: run `python -m paper_2302_12445_amd.build` "
                           "(there is no CPU fallback)")
+    # The device memory and streams handed to the library come from torch, so both must
+    # use ONE HIP runtime.  torch ships its own copy; loading it first makes libdear's
+    # dependency on libamdhip64.so.7 resolve to that copy instead of a second runtime.
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
     lib.dear_plan.argtypes = [C.POINTER(i64), i32, i32, i64, i32, C.POINTER(vp)]
