@@ -46,6 +46,43 @@ struct dear_ctx_impl {
 
 // ------------------------------------------------------------------------------- kernels
 
+// Launch-shape and cache-hint choices, fixed at build time (measured on MI355X; the
+// defaults are the fastest found).  *_U = 16-byte vectors per lane; a tile of
+// DEAR_TILE_ELEMS is shared by TILE_VECS / (U * DEAR_BLOCK) workgroups.
+#ifndef DEAR_RS_U_F32
+#define DEAR_RS_U_F32 4
+#endif
+#ifndef DEAR_RS_U_BF16
+#define DEAR_RS_U_BF16 2
+#endif
+#ifndef DEAR_RS_NT_LOAD
+#define DEAR_RS_NT_LOAD 1
+#endif
+#ifndef DEAR_RS_NT_STORE
+#define DEAR_RS_NT_STORE 1
+#endif
+#ifndef DEAR_AG_U
+#define DEAR_AG_U 1
+#endif
+#ifndef DEAR_AG_NT_LOAD
+#define DEAR_AG_NT_LOAD 0
+#endif
+#ifndef DEAR_AG_CHUNK_BYTES
+#define DEAR_AG_CHUNK_BYTES (8 << 20)  // shard bytes whose P copies are written back to back
+#endif
+#ifndef DEAR_AG_NT_STORE
+#define DEAR_AG_NT_STORE 1
+#endif
+#ifndef DEAR_UPD_U
+#define DEAR_UPD_U 2
+#endif
+#ifndef DEAR_UPD_NT_LOAD
+#define DEAR_UPD_NT_LOAD 1
+#endif
+#ifndef DEAR_UPD_NT_STORE
+#define DEAR_UPD_NT_STORE 1
+#endif
+
 // Pointers read from the pointer tables are generic; every tensor lives in global
 // memory, and saying so lets the compiler use global_load / global_store.
 #define DEAR_GLOBAL __attribute__((address_space(1)))
@@ -53,6 +90,41 @@ typedef const DEAR_GLOBAL u4 *global_u4_in;
 typedef DEAR_GLOBAL f4 *global_f4_out;
 typedef const DEAR_GLOBAL f4_dword_aligned *global_f4u_in;
 typedef DEAR_GLOBAL f4_dword_aligned *global_f4u_out;
+
+template <bool NT, class Ptr>
+__device__ __forceinline__ auto load_vec(Ptr p)
+{
+    if (NT) return __builtin_nontemporal_load(p);
+    return *p;
+}
+
+template <bool NT, class Ptr, class V>
+__device__ __forceinline__ void store_vec(Ptr p, V v)
+{
+    if (NT)
+        __builtin_nontemporal_store(v, p);
+    else
+        *p = v;
+}
+
+// 16-byte accesses to shard buffers, whose addresses are only 4-byte aligned.
+template <bool NT>
+__device__ __forceinline__ f4 load_f4_dword_aligned(const float *p)
+{
+    global_f4u_in q = (global_f4u_in)p;
+    if (NT) return __builtin_nontemporal_load(q);
+    return *q;
+}
+
+template <bool NT>
+__device__ __forceinline__ void store_f4_dword_aligned(float *p, f4 v)
+{
+    global_f4u_out q = (global_f4u_out)p;
+    if (NT)
+        __builtin_nontemporal_store(v, q);
+    else
+        *q = v;
+}
 
 __device__ __forceinline__ int ring_worker(int start, int k, int P)
 {
@@ -86,18 +158,19 @@ __device__ __forceinline__ void add_vector(float (&acc)[VE], const u4 r)
     }
 }
 
-// Body of the reduce-scatter for one tile.  ALL_FULL: the tile is a whole, aligned
-// DEAR_TILE_ELEMS run, so no lane needs an edge check.  CH replicas are loaded per lane
-// and vector before they are added; TAIL says P is not a multiple of CH.
-template <bool BF16, int CH, bool TAIL, bool ALL_FULL>
-__device__ __forceinline__ void reduce_scatter_tile(const dear_tile &t, const void *const *__restrict__ grad_tab,
-                                                    int L, int P, float inv_P, float *__restrict__ dst)
+// Body of the reduce-scatter for one workgroup's part of a tile.  ALL_FULL: the tile is a
+// whole, aligned DEAR_TILE_ELEMS run, so no lane needs an edge check.  CH replicas are
+// loaded per lane and vector before they are added; TAIL says P is not a multiple of CH.
+template <bool BF16, int U, int CH, bool TAIL, bool ALL_FULL>
+__device__ __forceinline__ void reduce_scatter_tile(const dear_tile &t, int part,
+                                                    const void *const *__restrict__ grad_tab, int L,
+                                                    int P, float inv_P, float *__restrict__ dst)
 {
-    constexpr int VE = BF16 ? 8 : 4;                       // elements per 16-byte vector
-    constexpr int U = DEAR_TILE_ELEMS / (VE * DEAR_BLOCK);  // vectors per lane
+    constexpr int VE = BF16 ? 8 : 4;  // elements per 16-byte vector
     const int tid = threadIdx.x;
     const int64_t a = t.src_begin, c = a + t.count;
-    const int64_t v_first = a / VE;
+    const int64_t v_first = a / VE + (int64_t)part * (U * DEAR_BLOCK);
+    if (!ALL_FULL && v_first * VE >= c) return;
     const int start = t.shard + 1 >= P ? 0 : t.shard + 1;
 
     int64_t vi[U];
@@ -125,7 +198,7 @@ __device__ __forceinline__ void reduce_scatter_tile(const dear_tile &t, const vo
             if (full[u]) {
 #pragma unroll
                 for (int kk = 0; kk < CH; ++kk)
-                    if (!TAIL || k0 + kk < P) raw[u][kk] = __builtin_nontemporal_load(src[kk] + vi[u]);
+                    if (!TAIL || k0 + kk < P) raw[u][kk] = load_vec<DEAR_RS_NT_LOAD>(src[kk] + vi[u]);
             }
 #pragma unroll
         for (int u = 0; u < U; ++u)
@@ -146,7 +219,7 @@ __device__ __forceinline__ void reduce_scatter_tile(const dear_tile &t, const vo
                 f4 r;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) r[j] = acc[u][4 * h + j] * inv_P;
-                *(global_f4u_out)(out + 4 * h) = r;
+                store_f4_dword_aligned<DEAR_RS_NT_STORE>(out + 4 * h, r);
             }
         } else if (e0 < c) {  // edge vector of the run: element by element
             for (int j = 0; j < VE; ++j) {
@@ -161,30 +234,33 @@ __device__ __forceinline__ void reduce_scatter_tile(const dear_tile &t, const vo
     }
 }
 
-// Reduce-scatter of one tile per workgroup (paper Sec. III-A; Eq. 2 for the 1/P).
+// Reduce-scatter (paper Sec. III-A; Eq. 2 for the 1/P).  SPLIT workgroups share a tile.
 // Summation starts at worker s+1 and ends with worker s, the order in which the ring
 // delivers the partial sums of chunk s to its owner.  The accumulator starts as -0.0f,
 // the additive identity that keeps the first addend's bits (including a -0.0f).
-template <bool BF16, int CH, bool TAIL>
+template <bool BF16, int U, int CH, bool TAIL>
 __global__ __launch_bounds__(DEAR_BLOCK) void reduce_scatter_kernel(
     const dear_tile *__restrict__ tiles, const void *const *__restrict__ grad_tab, int L, int P,
     float inv_P, float *__restrict__ shard_grad)
 {
-    const dear_tile t = tiles[blockIdx.x];
+    constexpr int SPLIT = DEAR_TILE_ELEMS / ((BF16 ? 8 : 4) * DEAR_BLOCK * U);
+    static_assert(SPLIT >= 1 && (SPLIT & (SPLIT - 1)) == 0, "U must divide the tile");
+    const dear_tile t = tiles[blockIdx.x / SPLIT];
+    const int part = blockIdx.x % SPLIT;
     float *__restrict__ dst = shard_grad + t.dst_begin;
     if (t.layer < 0) {  // padding slots reduce to +0
-        for (int i = threadIdx.x; i < t.count; i += DEAR_BLOCK) dst[i] = 0.0f;
+        for (int i = part * DEAR_BLOCK + threadIdx.x; i < t.count; i += SPLIT * DEAR_BLOCK) dst[i] = 0.0f;
         return;
     }
     if (t.count == DEAR_TILE_ELEMS)
-        reduce_scatter_tile<BF16, CH, TAIL, true>(t, grad_tab, L, P, inv_P, dst);
+        reduce_scatter_tile<BF16, U, CH, TAIL, true>(t, part, grad_tab, L, P, inv_P, dst);
     else
-        reduce_scatter_tile<BF16, CH, TAIL, false>(t, grad_tab, L, P, inv_P, dst);
+        reduce_scatter_tile<BF16, U, CH, TAIL, false>(t, part, grad_tab, L, P, inv_P, dst);
 }
 
 // SGD with momentum on contiguous shard slots (paper Eq. 1-2): v = mu*v + g; w = w - lr*v.
 // blockIdx.y selects the row (worker); each row segment is `vecs` 16-byte vectors long.
-constexpr int UPD_U = 4;
+constexpr int UPD_U = DEAR_UPD_U;
 __global__ __launch_bounds__(DEAR_BLOCK) void shard_update_kernel(
     const float *__restrict__ g, float *__restrict__ w, float *__restrict__ v, int64_t row_stride,
     int64_t base, int64_t vecs, float lr, float mu)
@@ -199,9 +275,9 @@ __global__ __launch_bounds__(DEAR_BLOCK) void shard_update_kernel(
     for (int u = 0; u < UPD_U; ++u) {
         const int64_t i = first + u * DEAR_BLOCK;
         if (i < vecs) {
-            gg[u] = __builtin_nontemporal_load(g4 + i);
-            ww[u] = __builtin_nontemporal_load(w4 + i);
-            vv[u] = __builtin_nontemporal_load(v4 + i);
+            gg[u] = load_vec<DEAR_UPD_NT_LOAD>(g4 + i);
+            ww[u] = load_vec<DEAR_UPD_NT_LOAD>(w4 + i);
+            vv[u] = load_vec<DEAR_UPD_NT_LOAD>(v4 + i);
         }
     }
 #pragma unroll
@@ -216,66 +292,72 @@ __global__ __launch_bounds__(DEAR_BLOCK) void shard_update_kernel(
                 const float t2 = lr * nv[j];
                 nw[j] = ww[u][j] - t2;
             }
-            v4[i] = nv;
-            w4[i] = nw;
+            store_vec<DEAR_UPD_NT_STORE>(v4 + i, nv);
+            store_vec<DEAR_UPD_NT_STORE>(w4 + i, nw);
         }
     }
 }
 
-// All-gather of one tile per workgroup with the copy-back to the layer tensors folded in
-// (paper Sec. III-A, IV-A): each shard value is read once and stored to all P replicas.
-template <bool ALL_FULL>
-__device__ __forceinline__ void all_gather_tile(const dear_tile &t, float *const *__restrict__ param_tab,
-                                                int L, int P, const float *__restrict__ src)
+// All-gather with the copy-back to the layer tensors folded in (paper Sec. III-A, IV-A).
+//
+// One workgroup copies one part of one tile to ONE replica.  Workgroups are ordered
+// (chunk, replica, part): the hardware starts workgroups in index order, so at any moment
+// the chip writes a long sequential run of one or two replicas instead of P interleaved
+// streams, which HBM sustains markedly better; the chunk's shard values (AG_CHUNK_WG
+// parts, a few MiB) are re-read for replicas 1..P-1 from L2 / Infinity Cache, not HBM.
+template <int U, bool ALL_FULL>
+__device__ __forceinline__ void all_gather_tile(const dear_tile &t, int part, DEAR_GLOBAL float *out,
+                                                const float *__restrict__ src)
 {
     constexpr int VE = 4;
-    constexpr int U = DEAR_TILE_ELEMS / (VE * DEAR_BLOCK);
     const int tid = threadIdx.x;
     const int64_t a = t.src_begin, c = a + t.count;
-    const int64_t v_first = a / VE;
-
-    int64_t vi[U];
-    bool full[U];
-    f4 val[U];
+    const int64_t v_first = a / VE + (int64_t)part * (U * DEAR_BLOCK);
+    if (!ALL_FULL && v_first * VE >= c) return;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        vi[u] = v_first + u * DEAR_BLOCK + tid;
-        const int64_t e0 = vi[u] * VE;
-        full[u] = ALL_FULL || (e0 >= a && e0 + VE <= c);
-        if (full[u]) val[u] = __builtin_nontemporal_load((global_f4u_in)(src + (e0 - a)));
-    }
-    for (int p = 0; p < P; ++p) {
-        global_f4_out out = (global_f4_out)param_tab[(size_t)p * L + t.layer];
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (full[u]) __builtin_nontemporal_store(val[u], out + vi[u]);
-    }
-    if (ALL_FULL) return;
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int64_t e0 = vi[u] * VE;
-        if (!full[u] && e0 < c) {
+        const int64_t vi = v_first + u * DEAR_BLOCK + tid;
+        const int64_t e0 = vi * VE;
+        if (ALL_FULL || (e0 >= a && e0 + VE <= c)) {
+            const f4 val = load_f4_dword_aligned<DEAR_AG_NT_LOAD>(src + (e0 - a));
+            store_vec<DEAR_AG_NT_STORE>((global_f4_out)out + vi, val);
+        } else if (e0 < c) {
             for (int j = 0; j < VE; ++j) {
                 const int64_t e = e0 + j;
-                if (e < a || e >= c) continue;
-                const float x = src[e - a];
-                for (int p = 0; p < P; ++p) ((DEAR_GLOBAL float *)param_tab[(size_t)p * L + t.layer])[e] = x;
+                if (e >= a && e < c) out[e] = src[e - a];
             }
         }
     }
 }
 
+constexpr int AG_U = DEAR_AG_U;
+constexpr int AG_SPLIT = DEAR_TILE_ELEMS / (4 * DEAR_BLOCK * AG_U);
+static_assert(AG_SPLIT >= 1 && (AG_SPLIT & (AG_SPLIT - 1)) == 0, "DEAR_AG_U must divide the tile");
+constexpr int AG_CHUNK_WG = DEAR_AG_CHUNK_BYTES / (16 * DEAR_BLOCK * AG_U);  // parts per chunk
+
+// n_parts = tiles * AG_SPLIT; the grid has n_parts * P workgroups.
 __global__ __launch_bounds__(DEAR_BLOCK) void all_gather_kernel(
     const dear_tile *__restrict__ tiles, float *const *__restrict__ param_tab, int L, int P,
-    const float *__restrict__ shard_param)
+    const float *__restrict__ shard_param, unsigned n_parts)
 {
-    const dear_tile t = tiles[blockIdx.x];
+    // blockIdx -> (chunk, replica p, part within chunk); the last chunk may be short
+    const unsigned per_chunk = AG_CHUNK_WG * (unsigned)P;
+    const unsigned chunk = blockIdx.x / per_chunk;
+    const unsigned r = blockIdx.x - chunk * per_chunk;
+    const unsigned first = chunk * AG_CHUNK_WG;
+    const unsigned len = n_parts - first < AG_CHUNK_WG ? n_parts - first : AG_CHUNK_WG;
+    const unsigned p = r / len;
+    const unsigned id = first + (r - p * len);
+
+    const dear_tile t = tiles[id / AG_SPLIT];
+    const int part = id % AG_SPLIT;
     if (t.layer < 0) return;
     const float *__restrict__ src = shard_param + t.dst_begin;
+    DEAR_GLOBAL float *out = (DEAR_GLOBAL float *)param_tab[(size_t)p * L + t.layer];
     if (t.count == DEAR_TILE_ELEMS)
-        all_gather_tile<true>(t, param_tab, L, P, src);
+        all_gather_tile<AG_U, true>(t, part, out, src);
     else
-        all_gather_tile<false>(t, param_tab, L, P, src);
+        all_gather_tile<AG_U, false>(t, part, out, src);
 }
 
 // Inverse of the all-gather for one worker: layer tensors -> owned shard slots.
@@ -342,30 +424,24 @@ void tile_range(const dear_ctx_impl *c, int32_t bucket, int64_t &first, int64_t 
 int launch_status() { return hipGetLastError() == hipSuccess ? DEAR_OK : DEAR_EHIP; }
 
 template <bool BF16>
-void rs_launch_dtype(int P, dim3 grid, dim3 block, hipStream_t st, const dear_tile *tiles,
+void rs_launch_dtype(int P, int64_t n_tiles, hipStream_t st, const dear_tile *tiles,
                      const void *const *grad_tab, int L, float inv_P, float *shard_grad)
 {
+    constexpr int U = BF16 ? DEAR_RS_U_BF16 : DEAR_RS_U_F32;
+    constexpr int SPLIT = DEAR_TILE_ELEMS / ((BF16 ? 8 : 4) * DEAR_BLOCK * U);
+    const dim3 grid(static_cast<unsigned>(n_tiles * SPLIT)), block(DEAR_BLOCK);
     // replicas per load batch: the largest of 8/4/2/1 that divides P without a tail when
     // P is small or a multiple of 4; otherwise batches of 8 with a predicated tail
     if (P % 8 == 0)
-        reduce_scatter_kernel<BF16, 8, false><<<grid, block, 0, st>>>(tiles, grad_tab, L, P, inv_P, shard_grad);
+        reduce_scatter_kernel<BF16, U, 8, false><<<grid, block, 0, st>>>(tiles, grad_tab, L, P, inv_P, shard_grad);
     else if (P % 4 == 0)
-        reduce_scatter_kernel<BF16, 4, false><<<grid, block, 0, st>>>(tiles, grad_tab, L, P, inv_P, shard_grad);
+        reduce_scatter_kernel<BF16, U, 4, false><<<grid, block, 0, st>>>(tiles, grad_tab, L, P, inv_P, shard_grad);
     else if (P == 2)
-        reduce_scatter_kernel<BF16, 2, false><<<grid, block, 0, st>>>(tiles, grad_tab, L, P, inv_P, shard_grad);
+        reduce_scatter_kernel<BF16, U, 2, false><<<grid, block, 0, st>>>(tiles, grad_tab, L, P, inv_P, shard_grad);
     else if (P == 1)
-        reduce_scatter_kernel<BF16, 1, false><<<grid, block, 0, st>>>(tiles, grad_tab, L, P, inv_P, shard_grad);
+        reduce_scatter_kernel<BF16, U, 1, false><<<grid, block, 0, st>>>(tiles, grad_tab, L, P, inv_P, shard_grad);
     else
-        reduce_scatter_kernel<BF16, 8, true><<<grid, block, 0, st>>>(tiles, grad_tab, L, P, inv_P, shard_grad);
-}
-
-void rs_launch(bool bf16, int P, dim3 grid, dim3 block, hipStream_t st, const dear_tile *tiles,
-               const void *const *grad_tab, int L, float inv_P, float *shard_grad)
-{
-    if (bf16)
-        rs_launch_dtype<true>(P, grid, block, st, tiles, grad_tab, L, inv_P, shard_grad);
-    else
-        rs_launch_dtype<false>(P, grid, block, st, tiles, grad_tab, L, inv_P, shard_grad);
+        reduce_scatter_kernel<BF16, U, 8, true><<<grid, block, 0, st>>>(tiles, grad_tab, L, P, inv_P, shard_grad);
 }
 
 }  // namespace
@@ -399,7 +475,7 @@ extern "C" int dear_ctx_create(const dear_plan_t *plan, int32_t grad_dtype,
     } catch (const std::bad_alloc &) {
         return DEAR_ENOMEM;
     }
-    if (tiles.size() > 0x7fffffffu) return DEAR_EINVAL;  // grid.x limit
+    if (tiles.size() > 0x7fffffffu / 16) return DEAR_EINVAL;  // grid.x limit, up to 16 workgroups a tile
     if (hipGetDevice(&c->device) != hipSuccess) return DEAR_EHIP;
 
     const size_t tile_bytes = tiles.size() * sizeof(dear_tile), ptr_bytes = n_ptr * sizeof(void *);
@@ -444,8 +520,10 @@ extern "C" int dear_reduce_scatter(dear_ctx_t *c, int32_t bucket, float *shard_g
     if (count == 0) return DEAR_OK;
     const float inv_P = 1.0f / static_cast<float>(c->P);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const dim3 grid(static_cast<unsigned>(count)), block(DEAR_BLOCK);
-    rs_launch(c->g == 2, c->P, grid, block, st, c->d_tiles + first, c->d_grad, c->L, inv_P, shard_grad);
+    if (c->g == 2)
+        rs_launch_dtype<true>(c->P, count, st, c->d_tiles + first, c->d_grad, c->L, inv_P, shard_grad);
+    else
+        rs_launch_dtype<false>(c->P, count, st, c->d_tiles + first, c->d_grad, c->L, inv_P, shard_grad);
     return launch_status();
 }
 
@@ -486,9 +564,11 @@ extern "C" int dear_all_gather(dear_ctx_t *c, int32_t bucket, const float *shard
     int64_t first, count;
     tile_range(c, bucket, first, count);
     if (count == 0) return DEAR_OK;
-    all_gather_kernel<<<dim3(static_cast<unsigned>(count)), dim3(DEAR_BLOCK), 0,
+    const int64_t n_parts = count * AG_SPLIT;
+    if (n_parts * c->P > 0x7fffffff) return DEAR_EINVAL;
+    all_gather_kernel<<<dim3(static_cast<unsigned>(n_parts * c->P)), dim3(DEAR_BLOCK), 0,
                         static_cast<hipStream_t>(hip_stream)>>>(c->d_tiles + first, c->d_param, c->L, c->P,
-                                                                shard_param);
+                                                                shard_param, static_cast<unsigned>(n_parts));
     return launch_status();
 }
 
