@@ -45,6 +45,9 @@ def parse_args():
     ap.add_argument("--launch", default="per_bucket", choices=["per_bucket", "all_buckets"],
                     help="one launch per bucket and phase (the DeAR schedule) or one per phase")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run three plain 1 GiB device copies (torch) so that a counter "
+                         "profile of this command holds a dispatch of known traffic")
     ap.add_argument("--sample-buckets", type=int, default=2,
                     help="buckets (from bucket 0) the CPU oracle is timed on")
     return ap.parse_args()
@@ -142,6 +145,14 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline_and_check(em, w, args.sample_buckets)
+
+    if args.pmc_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=device)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         em.iteration(w.lr, w.momentum, per_bucket=per_bucket)

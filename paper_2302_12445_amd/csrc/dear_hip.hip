@@ -209,6 +209,35 @@ __device__ __forceinline__ void reduce_scatter_tile(const dear_tile &t, int part
             }
     }
 
+    if (BF16 && ALL_FULL) {
+        // A lane holds 8 results = 32 bytes, so storing them directly would leave each
+        // store instruction half dense (16 of every 32 bytes) and HBM would see partial
+        // lines.  Each wavefront turns its 512 results through its own 2 KiB of LDS so
+        // that both store instructions write 64 consecutive 16-byte pieces.
+        __shared__ float stage[DEAR_BLOCK / 64][64 * 8];
+        const int wave = tid >> 6, lane = tid & 63;
+        float *sw = stage[wave];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            f4 lo, hi;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                lo[j] = acc[u][j] * inv_P;
+                hi[j] = acc[u][4 + j] * inv_P;
+            }
+            *reinterpret_cast<f4 *>(sw + 8 * lane) = lo;
+            *reinterpret_cast<f4 *>(sw + 8 * lane + 4) = hi;
+            __syncthreads();
+            const f4 o0 = *reinterpret_cast<const f4 *>(sw + 4 * lane);
+            const f4 o1 = *reinterpret_cast<const f4 *>(sw + 256 + 4 * lane);
+            __syncthreads();
+            float *out = dst + ((v_first + u * DEAR_BLOCK + wave * 64) * VE - a);  // wave's first element
+            store_f4_dword_aligned<DEAR_RS_NT_STORE>(out + 4 * lane, o0);
+            store_f4_dword_aligned<DEAR_RS_NT_STORE>(out + 256 + 4 * lane, o1);
+        }
+        return;
+    }
+
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int64_t e0 = vi[u] * VE;
