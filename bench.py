@@ -31,9 +31,14 @@ import torch
 import workloads as W
 
 HBM_PEAK_GBPS = 8000.0
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs (see profiles/); filled in per workload once measured, else null.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per launch (average over the buckets) from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs of this benchmark, each scaled by what the counter reads for a plain
+# 1 GiB device copy (fetch x2.0000, write x1.0000); summaries in profiles/.
+MEASURED_TRAFFIC_BYTES = {
+    ("bert_large", "rs"): 612670396, ("bert_large", "update"): 611343011, ("bert_large", "ag"): 1106461643,
+    ("resnet50", "rs"): 184355646, ("resnet50", "update"): 102255704, ("resnet50", "ag"): 187511994,
+    ("bert_base", "rs"): 1070366899, ("bert_base", "update"): 314614881, ("bert_base", "ag"): 1073750463,
+}
 
 
 def parse_args():
@@ -196,7 +201,7 @@ def main():
     roofline = {
         "bound": "hbm", "kernel": kernel_of[dom], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
         "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-        "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
+        "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom)) if per_bucket else None,
         "bytes_per_launch": bytes_[dom] // launches, "launches_per_step": launches,
         "avg_launch_ms": round(phase_ms[dom] / launches, 4),
         "phases": {n: {"ms": round(phase_ms[n], 4), "GBps": round(bytes_[n] / (phase_ms[n] * 1e-3) / 1e9, 1)}
