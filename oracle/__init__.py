@@ -106,6 +106,15 @@ def _bucket_layers(pl: OraclePlan, buckets: Sequence[int]) -> List[int]:
     return out
 
 
+def _layers_of_shards(pl: OraclePlan, b: int, s0: int, s1: int) -> List[int]:
+    """Layers of bucket b that hold a position of shards s0 .. s1-1."""
+    S = int(pl.bucket_shard_len[b])
+    lo, hi = s0 * S, min(s1 * S, int(pl.bucket_len[b]))
+    first = int(pl.bucket_first_layer[b])
+    return [l for l in range(first, first + int(pl.bucket_n_layers[b]))
+            if int(pl.layer_offset[l]) < hi and int(pl.layer_offset[l]) + int(pl.sizes[l]) > lo]
+
+
 def _ptr_table(pl: OraclePlan, arrays: Sequence[Sequence[Optional[np.ndarray]]], layers: Sequence[int],
                dtype, workers: Optional[range] = None):
     """Host pointer table [p*L + l].  Only the listed layers (and workers) are needed by the
@@ -146,8 +155,9 @@ def reduce_scatter(pl: OraclePlan, bucket: int, grads: Sequence[Sequence[np.ndar
     stride = _check_rows(pl, shard_grad)
     want = np.float32 if pl.grad_elem_bytes == 4 else np.uint16
     todo = _buckets(pl, bucket, forward=False)
-    tab = _ptr_table(pl, grads, _bucket_layers(pl, todo), want)
     s0, s1 = (0, pl.P) if shards is None else (shards.start, shards.stop)
+    needed = [l for b in todo for l in _layers_of_shards(pl, b, s0, s1)]
+    tab = _ptr_table(pl, grads, needed, want)
     for b in todo:
         lib.oracle_reduce_scatter(
             _p(pl.sizes, C.c_int64), C.c_int32(pl.L), C.c_int32(pl.P), C.c_int32(pl.grad_elem_bytes),
