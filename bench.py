@@ -188,6 +188,25 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
+    # the same steps with reduce-scatter and update of a bucket in one kernel (gbar stays in
+    # registers): reported beside the headline, never as `value`
+    fev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    buckets = list(range(nb)) if per_bucket else [-1]
+    for _ in range(2):
+        em.iteration(w.lr, w.momentum, per_bucket=per_bucket, fused_update=True)
+    torch.cuda.synchronize()
+    f0 = time.perf_counter()
+    for k in range(args.steps):
+        fev[k][0].record()
+        for b in buckets:
+            em.reduce_scatter_update(b, w.lr, w.momentum)
+        fev[k][1].record()
+        for b in reversed(buckets):
+            em.all_gather(b)
+        fev[k][2].record()
+    torch.cuda.synchronize()
+    fwall = time.perf_counter() - f0
+
     bytes_ = w.algorithmic_bytes()
     ms_per_step = wall * 1e3 / args.steps
     value = bytes_["total"] / (wall / args.steps) / 1e9
@@ -219,6 +238,17 @@ def main():
                    "grad_dtype": w.grad_dtype, "launch": args.launch,
                    "algorithmic_bytes_per_step": bytes_["total"]},
         "roofline": roofline,
+    }
+    f_rs = sum(fev[k][0].elapsed_time(fev[k][1]) for k in range(args.steps)) / args.steps
+    f_ag = sum(fev[k][1].elapsed_time(fev[k][2]) for k in range(args.steps)) / args.steps
+    fused_rs_bytes = bytes_["rs"] + bytes_["update"] - 8 * w.N   # gbar neither written nor re-read
+    line["fused_rs_update"] = {
+        "note": "dear_reduce_scatter_update + dear_all_gather; moves 8N fewer bytes than the headline path",
+        "ms_per_step": round(fwall * 1e3 / args.steps, 4),
+        "effective_GBps_on_headline_bytes": round(bytes_["total"] / (fwall / args.steps) / 1e9, 1),
+        "moved_GBps": round((bytes_["total"] - 8 * w.N) / (fwall / args.steps) / 1e9, 1),
+        "phases": {"rs_update": {"ms": round(f_rs, 4), "GBps": round(fused_rs_bytes / (f_rs * 1e-3) / 1e9, 1)},
+                   "ag": {"ms": round(f_ag, 4), "GBps": round(bytes_["ag"] / (f_ag * 1e-3) / 1e9, 1)}},
     }
     if cpu is not None:
         line["cpu_baseline"] = cpu

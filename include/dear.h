@@ -200,6 +200,20 @@ int dear_shard_update(dear_ctx_t *ctx, int32_t bucket, const float *shard_grad,
                       void *hip_stream);
 
 /* ---------------------------------------------------------------------------------
+ * dear_reduce_scatter_update -- dear_reduce_scatter and dear_shard_update of a bucket in
+ * one kernel: the averaged gradient of a slot is consumed by the slot's update while it
+ * is still in registers and is never written to memory (no shard_grad buffer).  Same
+ * operations in the same order as the two separate calls, so shard_param and shard_mom
+ * come out bit-identical.  It still runs in the backward pass, before any all-gather
+ * (paper Section III-B), so the decoupling of the two halves is untouched.
+ *   shard_param, shard_mom  device, updated in place (padding slots are updated with
+ *                           an averaged gradient of +0.0f)
+ * Errors: DEAR_EINVAL, DEAR_ERANGE, DEAR_EALIGN, DEAR_EHIP.
+ */
+int dear_reduce_scatter_update(dear_ctx_t *ctx, int32_t bucket, float *shard_param, float *shard_mom,
+                               float lr, float momentum, void *hip_stream);
+
+/* ---------------------------------------------------------------------------------
  * dear_all_gather -- second half of the decoupled all-reduce, with the copy from the
  * fusion buffer back to the original tensors folded into the stores.
  *

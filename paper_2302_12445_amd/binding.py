@@ -22,8 +22,8 @@ DEAR_SHARD_ALIGN = 32
 EXPORTS = [
     "dear_plan", "dear_plan_fixed_layers", "dear_plan_free", "dear_plan_view", "dear_plan_tiles",
     "dear_ctx_create", "dear_ctx_destroy",
-    "dear_reduce_scatter", "dear_shard_update", "dear_all_gather", "dear_scatter_params",
-    "dear_strerror", "dear_version",
+    "dear_reduce_scatter", "dear_reduce_scatter_update", "dear_shard_update", "dear_all_gather",
+    "dear_scatter_params", "dear_strerror", "dear_version",
 ]
 
 
@@ -80,13 +80,14 @@ def load_library() -> C.CDLL:
     lib.dear_ctx_destroy.restype = None
     lib.dear_reduce_scatter.argtypes = [vp, i32, vp, vp]
     lib.dear_shard_update.argtypes = [vp, i32, vp, vp, vp, f32, f32, vp]
+    lib.dear_reduce_scatter_update.argtypes = [vp, i32, vp, vp, f32, f32, vp]
     lib.dear_all_gather.argtypes = [vp, i32, vp, vp]
     lib.dear_scatter_params.argtypes = [vp, i32, vp, vp]
     lib.dear_strerror.argtypes = [C.c_int]
     lib.dear_strerror.restype = C.c_char_p
     lib.dear_version.restype = C.c_int
     for name in ("dear_plan", "dear_plan_fixed_layers", "dear_plan_view", "dear_plan_tiles", "dear_ctx_create",
-                 "dear_reduce_scatter", "dear_shard_update", "dear_all_gather", "dear_scatter_params"):
+                 "dear_reduce_scatter", "dear_reduce_scatter_update", "dear_shard_update", "dear_all_gather", "dear_scatter_params"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -226,6 +227,13 @@ def dear_shard_update(ctx: Context, bucket: int, shard_grad: int, shard_param: i
     _check(load_library().dear_shard_update(ctx.handle, bucket, C.c_void_p(shard_grad),
                                             C.c_void_p(shard_param), C.c_void_p(shard_mom),
                                             lr, momentum, _stream(stream)), "dear_shard_update")
+
+
+def dear_reduce_scatter_update(ctx: Context, bucket: int, shard_param: int, shard_mom: int,
+                               lr: float, momentum: float, stream: Optional[int] = None) -> None:
+    _check(load_library().dear_reduce_scatter_update(ctx.handle, bucket, C.c_void_p(shard_param),
+                                                     C.c_void_p(shard_mom), lr, momentum, _stream(stream)),
+           "dear_reduce_scatter_update")
 
 
 def dear_all_gather(ctx: Context, bucket: int, shard_param: int, stream: Optional[int] = None) -> None:

@@ -158,16 +158,76 @@ __device__ __forceinline__ void add_vector(float (&acc)[VE], const u4 r)
     }
 }
 
+// Where a reduce-scatter result goes.  Plain: gbar is stored to the gradient shard buffer.
+// FUSED: the SGD-momentum update of the slot is applied at once (v = mu*v + gbar;
+// w = w - lr*v, the same four separately rounded operations as shard_update_kernel) and gbar
+// is never written, which saves its 4-byte write and 4-byte re-read per element.
+template <bool FUSED>
+struct rs_sink {
+    float *__restrict__ g;  // plain: gradient shards
+    float *__restrict__ w;  // fused: parameter shards
+    float *__restrict__ v;  // fused: momentum shards
+    float lr, mu;
+};
+
+__device__ __forceinline__ void sgd_momentum(float gbar, float &w, float &v, float lr, float mu)
+{
+    const float t1 = mu * v;
+    v = t1 + gbar;
+    const float t2 = lr * v;
+    w = w - t2;
+}
+
+// One 16-byte piece of results at shard-buffer element index `idx` (4-byte aligned).
+// FUSED callers pass the slot's w and v, loaded early so the loads overlap the gradient loads.
+template <bool FUSED>
+__device__ __forceinline__ void emit_piece(const rs_sink<FUSED> &o, int64_t idx, f4 gbar, f4 w, f4 v)
+{
+    if (!FUSED) {
+        store_f4_dword_aligned<DEAR_RS_NT_STORE>(o.g + idx, gbar);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float wj = w[j], vj = v[j];
+            sgd_momentum(gbar[j], wj, vj, o.lr, o.mu);
+            w[j] = wj;
+            v[j] = vj;
+        }
+        store_f4_dword_aligned<DEAR_RS_NT_STORE>(o.v + idx, v);
+        store_f4_dword_aligned<DEAR_RS_NT_STORE>(o.w + idx, w);
+    }
+}
+
+template <bool FUSED>
+__device__ __forceinline__ void emit_elem(const rs_sink<FUSED> &o, int64_t idx, float gbar)
+{
+    if (!FUSED) {
+        o.g[idx] = gbar;
+    } else {
+        float w = o.w[idx], v = o.v[idx];
+        sgd_momentum(gbar, w, v, o.lr, o.mu);
+        o.v[idx] = v;
+        o.w[idx] = w;
+    }
+}
+
 // Body of the reduce-scatter for one workgroup's part of a tile.  ALL_FULL: the tile is a
 // whole, aligned DEAR_TILE_ELEMS run, so no lane needs an edge check.  CH replicas are
 // loaded per lane and vector before they are added; TAIL says P is not a multiple of CH.
-template <bool BF16, int U, int CH, bool TAIL, bool ALL_FULL>
+template <bool BF16, int U, int CH, bool TAIL, bool ALL_FULL, bool FUSED>
 __device__ __forceinline__ void reduce_scatter_tile(const dear_tile &t, int part,
                                                     const void *const *__restrict__ grad_tab, int L,
-                                                    int P, float inv_P, float *__restrict__ dst)
+                                                    int P, float inv_P, const rs_sink<FUSED> &o)
 {
     constexpr int VE = BF16 ? 8 : 4;  // elements per 16-byte vector
+    constexpr int PIECES = VE / 4;     // 16-byte result pieces per lane and vector
+    // bf16, whole tile: a lane's 8 results are 32 bytes, so storing them directly would
+    // leave each store instruction half dense (16 of every 32 bytes) and HBM would see
+    // partial lines.  Each wavefront turns its 512 results through its own 2 KiB of LDS
+    // so that both store instructions write 64 consecutive 16-byte pieces.
+    constexpr bool TURN = BF16 && ALL_FULL;
     const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
     const int64_t a = t.src_begin, c = a + t.count;
     const int64_t v_first = a / VE + (int64_t)part * (U * DEAR_BLOCK);
     if (!ALL_FULL && v_first * VE >= c) return;
@@ -175,7 +235,9 @@ __device__ __forceinline__ void reduce_scatter_tile(const dear_tile &t, int part
 
     int64_t vi[U];
     bool full[U];
+    int64_t piece_idx[U][PIECES];  // shard-buffer element index of each result piece
     float acc[U][VE];
+    f4 w_old[U][PIECES], v_old[U][PIECES];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         vi[u] = v_first + u * DEAR_BLOCK + tid;
@@ -183,6 +245,17 @@ __device__ __forceinline__ void reduce_scatter_tile(const dear_tile &t, int part
         full[u] = ALL_FULL || (e0 >= a && e0 + VE <= c);
 #pragma unroll
         for (int j = 0; j < VE; ++j) acc[u][j] = -0.0f;
+#pragma unroll
+        for (int h = 0; h < PIECES; ++h) {
+            if (TURN)  // piece h of the wave's 512-element run, lane-th 16 bytes of it
+                piece_idx[u][h] = t.dst_begin + (v_first + u * DEAR_BLOCK + wave * 64) * VE - a + 256 * h + 4 * lane;
+            else
+                piece_idx[u][h] = t.dst_begin + (e0 - a) + 4 * h;
+            if (FUSED && full[u]) {
+                w_old[u][h] = load_f4_dword_aligned<DEAR_RS_NT_LOAD>(o.w + piece_idx[u][h]);
+                v_old[u][h] = load_f4_dword_aligned<DEAR_RS_NT_LOAD>(o.v + piece_idx[u][h]);
+            }
+        }
     }
 
     for (int k0 = 0; k0 < P; k0 += CH) {
@@ -209,13 +282,8 @@ __device__ __forceinline__ void reduce_scatter_tile(const dear_tile &t, int part
             }
     }
 
-    if (BF16 && ALL_FULL) {
-        // A lane holds 8 results = 32 bytes, so storing them directly would leave each
-        // store instruction half dense (16 of every 32 bytes) and HBM would see partial
-        // lines.  Each wavefront turns its 512 results through its own 2 KiB of LDS so
-        // that both store instructions write 64 consecutive 16-byte pieces.
+    if constexpr (TURN) {
         __shared__ float stage[DEAR_BLOCK / 64][64 * 8];
-        const int wave = tid >> 6, lane = tid & 63;
         float *sw = stage[wave];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -231,9 +299,8 @@ __device__ __forceinline__ void reduce_scatter_tile(const dear_tile &t, int part
             const f4 o0 = *reinterpret_cast<const f4 *>(sw + 4 * lane);
             const f4 o1 = *reinterpret_cast<const f4 *>(sw + 256 + 4 * lane);
             __syncthreads();
-            float *out = dst + ((v_first + u * DEAR_BLOCK + wave * 64) * VE - a);  // wave's first element
-            store_f4_dword_aligned<DEAR_RS_NT_STORE>(out + 4 * lane, o0);
-            store_f4_dword_aligned<DEAR_RS_NT_STORE>(out + 256 + 4 * lane, o1);
+            emit_piece<FUSED>(o, piece_idx[u][0], o0, w_old[u][0], v_old[u][0]);
+            emit_piece<FUSED>(o, piece_idx[u][PIECES - 1], o1, w_old[u][PIECES - 1], v_old[u][PIECES - 1]);
         }
         return;
     }
@@ -242,13 +309,12 @@ __device__ __forceinline__ void reduce_scatter_tile(const dear_tile &t, int part
     for (int u = 0; u < U; ++u) {
         const int64_t e0 = vi[u] * VE;
         if (full[u]) {
-            float *out = dst + (e0 - a);
 #pragma unroll
-            for (int h = 0; h < VE / 4; ++h) {
+            for (int h = 0; h < PIECES; ++h) {
                 f4 r;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) r[j] = acc[u][4 * h + j] * inv_P;
-                store_f4_dword_aligned<DEAR_RS_NT_STORE>(out + 4 * h, r);
+                emit_piece<FUSED>(o, piece_idx[u][h], r, w_old[u][h], v_old[u][h]);
             }
         } else if (e0 < c) {  // edge vector of the run: element by element
             for (int j = 0; j < VE; ++j) {
@@ -257,7 +323,7 @@ __device__ __forceinline__ void reduce_scatter_tile(const dear_tile &t, int part
                 float s = -0.0f;
                 for (int k = 0; k < P; ++k)
                     s = s + grad_elem<BF16>(grad_tab[(size_t)ring_worker(start, k, P) * L + t.layer], e);
-                dst[e - a] = s * inv_P;
+                emit_elem<FUSED>(o, t.dst_begin + (e - a), s * inv_P);
             }
         }
     }
@@ -267,24 +333,24 @@ __device__ __forceinline__ void reduce_scatter_tile(const dear_tile &t, int part
 // Summation starts at worker s+1 and ends with worker s, the order in which the ring
 // delivers the partial sums of chunk s to its owner.  The accumulator starts as -0.0f,
 // the additive identity that keeps the first addend's bits (including a -0.0f).
-template <bool BF16, int U, int CH, bool TAIL>
+template <bool BF16, int U, int CH, bool TAIL, bool FUSED>
 __global__ __launch_bounds__(DEAR_BLOCK) void reduce_scatter_kernel(
     const dear_tile *__restrict__ tiles, const void *const *__restrict__ grad_tab, int L, int P,
-    float inv_P, float *__restrict__ shard_grad)
+    float inv_P, const rs_sink<FUSED> o)
 {
     constexpr int SPLIT = DEAR_TILE_ELEMS / ((BF16 ? 8 : 4) * DEAR_BLOCK * U);
     static_assert(SPLIT >= 1 && (SPLIT & (SPLIT - 1)) == 0, "U must divide the tile");
     const dear_tile t = tiles[blockIdx.x / SPLIT];
     const int part = blockIdx.x % SPLIT;
-    float *__restrict__ dst = shard_grad + t.dst_begin;
-    if (t.layer < 0) {  // padding slots reduce to +0
-        for (int i = part * DEAR_BLOCK + threadIdx.x; i < t.count; i += SPLIT * DEAR_BLOCK) dst[i] = 0.0f;
+    if (t.layer < 0) {  // padding slots: gbar = +0
+        for (int i = part * DEAR_BLOCK + threadIdx.x; i < t.count; i += SPLIT * DEAR_BLOCK)
+            emit_elem<FUSED>(o, t.dst_begin + i, 0.0f);
         return;
     }
     if (t.count == DEAR_TILE_ELEMS)
-        reduce_scatter_tile<BF16, U, CH, TAIL, true>(t, part, grad_tab, L, P, inv_P, dst);
+        reduce_scatter_tile<BF16, U, CH, TAIL, true, FUSED>(t, part, grad_tab, L, P, inv_P, o);
     else
-        reduce_scatter_tile<BF16, U, CH, TAIL, false>(t, part, grad_tab, L, P, inv_P, dst);
+        reduce_scatter_tile<BF16, U, CH, TAIL, false, FUSED>(t, part, grad_tab, L, P, inv_P, o);
 }
 
 // SGD with momentum on contiguous shard slots (paper Eq. 1-2): v = mu*v + g; w = w - lr*v.
@@ -452,25 +518,26 @@ void tile_range(const dear_ctx_impl *c, int32_t bucket, int64_t &first, int64_t 
 
 int launch_status() { return hipGetLastError() == hipSuccess ? DEAR_OK : DEAR_EHIP; }
 
-template <bool BF16>
-void rs_launch_dtype(int P, int64_t n_tiles, hipStream_t st, const dear_tile *tiles,
-                     const void *const *grad_tab, int L, float inv_P, float *shard_grad)
+template <bool BF16, bool FUSED>
+void rs_launch(int P, int64_t n_tiles, hipStream_t st, const dear_tile *tiles,
+               const void *const *grad_tab, int L, const rs_sink<FUSED> &o)
 {
     constexpr int U = BF16 ? DEAR_RS_U_BF16 : DEAR_RS_U_F32;
     constexpr int SPLIT = DEAR_TILE_ELEMS / ((BF16 ? 8 : 4) * DEAR_BLOCK * U);
     const dim3 grid(static_cast<unsigned>(n_tiles * SPLIT)), block(DEAR_BLOCK);
+    const float inv_P = 1.0f / static_cast<float>(P);
     // replicas per load batch: the largest of 8/4/2/1 that divides P without a tail when
     // P is small or a multiple of 4; otherwise batches of 8 with a predicated tail
     if (P % 8 == 0)
-        reduce_scatter_kernel<BF16, U, 8, false><<<grid, block, 0, st>>>(tiles, grad_tab, L, P, inv_P, shard_grad);
+        reduce_scatter_kernel<BF16, U, 8, false, FUSED><<<grid, block, 0, st>>>(tiles, grad_tab, L, P, inv_P, o);
     else if (P % 4 == 0)
-        reduce_scatter_kernel<BF16, U, 4, false><<<grid, block, 0, st>>>(tiles, grad_tab, L, P, inv_P, shard_grad);
+        reduce_scatter_kernel<BF16, U, 4, false, FUSED><<<grid, block, 0, st>>>(tiles, grad_tab, L, P, inv_P, o);
     else if (P == 2)
-        reduce_scatter_kernel<BF16, U, 2, false><<<grid, block, 0, st>>>(tiles, grad_tab, L, P, inv_P, shard_grad);
+        reduce_scatter_kernel<BF16, U, 2, false, FUSED><<<grid, block, 0, st>>>(tiles, grad_tab, L, P, inv_P, o);
     else if (P == 1)
-        reduce_scatter_kernel<BF16, U, 1, false><<<grid, block, 0, st>>>(tiles, grad_tab, L, P, inv_P, shard_grad);
+        reduce_scatter_kernel<BF16, U, 1, false, FUSED><<<grid, block, 0, st>>>(tiles, grad_tab, L, P, inv_P, o);
     else
-        reduce_scatter_kernel<BF16, U, 8, true><<<grid, block, 0, st>>>(tiles, grad_tab, L, P, inv_P, shard_grad);
+        reduce_scatter_kernel<BF16, U, 8, true, FUSED><<<grid, block, 0, st>>>(tiles, grad_tab, L, P, inv_P, o);
 }
 
 }  // namespace
@@ -547,12 +614,32 @@ extern "C" int dear_reduce_scatter(dear_ctx_t *c, int32_t bucket, float *shard_g
     int64_t first, count;
     tile_range(c, bucket, first, count);
     if (count == 0) return DEAR_OK;
-    const float inv_P = 1.0f / static_cast<float>(c->P);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const rs_sink<false> o{shard_grad, nullptr, nullptr, 0.0f, 0.0f};
     if (c->g == 2)
-        rs_launch_dtype<true>(c->P, count, st, c->d_tiles + first, c->d_grad, c->L, inv_P, shard_grad);
+        rs_launch<true, false>(c->P, count, st, c->d_tiles + first, c->d_grad, c->L, o);
     else
-        rs_launch_dtype<false>(c->P, count, st, c->d_tiles + first, c->d_grad, c->L, inv_P, shard_grad);
+        rs_launch<false, false>(c->P, count, st, c->d_tiles + first, c->d_grad, c->L, o);
+    return launch_status();
+}
+
+extern "C" int dear_reduce_scatter_update(dear_ctx_t *c, int32_t bucket, float *shard_param,
+                                         float *shard_mom, float lr, float momentum, void *hip_stream)
+{
+    int rc = check_call(c, bucket);
+    if (rc == DEAR_OK) rc = check_shard_buffer(shard_param);
+    if (rc == DEAR_OK) rc = check_shard_buffer(shard_mom);
+    if (rc != DEAR_OK) return rc;
+    if (shard_param == shard_mom) return DEAR_EINVAL;
+    int64_t first, count;
+    tile_range(c, bucket, first, count);
+    if (count == 0) return DEAR_OK;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const rs_sink<true> o{nullptr, shard_param, shard_mom, lr, momentum};
+    if (c->g == 2)
+        rs_launch<true, true>(c->P, count, st, c->d_tiles + first, c->d_grad, c->L, o);
+    else
+        rs_launch<false, true>(c->P, count, st, c->d_tiles + first, c->d_grad, c->L, o);
     return launch_status();
 }
 

@@ -91,6 +91,10 @@ class EmulatedWorkers:
     def reduce_scatter(self, bucket: int = -1, stream=None) -> None:
         B.dear_reduce_scatter(self.ctx, bucket, self.shard_grad.data_ptr(), _stream_handle(stream))
 
+    def reduce_scatter_update(self, bucket: int, lr: float, momentum: float, stream=None) -> None:
+        B.dear_reduce_scatter_update(self.ctx, bucket, self.shard_param.data_ptr(), self.shard_mom.data_ptr(),
+                                     lr, momentum, _stream_handle(stream))
+
     def shard_update(self, bucket: int, lr: float, momentum: float, stream=None) -> None:
         B.dear_shard_update(self.ctx, bucket, self.shard_grad.data_ptr(), self.shard_param.data_ptr(),
                             self.shard_mom.data_ptr(), lr, momentum, _stream_handle(stream))
@@ -98,21 +102,22 @@ class EmulatedWorkers:
     def all_gather(self, bucket: int = -1, stream=None) -> None:
         B.dear_all_gather(self.ctx, bucket, self.shard_param.data_ptr(), _stream_handle(stream))
 
-    def iteration(self, lr: float, momentum: float, per_bucket: bool = True, stream=None) -> None:
+    def iteration(self, lr: float, momentum: float, per_bucket: bool = True, stream=None,
+                  fused_update: bool = False) -> None:
         """One pass of the whole path on one stream: reduce-scatter the buckets in the order
-        their gradients become ready, update the owned shards, all-gather in forward order."""
-        nb = self.plan.n_buckets
-        if per_bucket:
-            for b in range(nb):
-                self.reduce_scatter(b, stream)
-            for b in range(nb):
-                self.shard_update(b, lr, momentum, stream)
-            for b in reversed(range(nb)):
-                self.all_gather(b, stream)
+        their gradients become ready, update the owned shards, all-gather in forward order.
+        fused_update: reduce-scatter and update of a bucket in one kernel."""
+        buckets = list(range(self.plan.n_buckets)) if per_bucket else [-1]
+        if fused_update:
+            for b in buckets:
+                self.reduce_scatter_update(b, lr, momentum, stream)
         else:
-            self.reduce_scatter(-1, stream)
-            self.shard_update(-1, lr, momentum, stream)
-            self.all_gather(-1, stream)
+            for b in buckets:
+                self.reduce_scatter(b, stream)
+            for b in buckets:
+                self.shard_update(b, lr, momentum, stream)
+        for b in reversed(buckets):
+            self.all_gather(b, stream)
 
     def close(self) -> None:
         self.ctx.destroy()

@@ -88,7 +88,7 @@ class Pair:
         oracle.shard_update(self.op, -1, self.sg, self.sp, self.sm, w.lr, w.momentum)
         oracle.all_gather(self.op, -1, self.sp, self.params)
 
-    def run(self, iterations=3, per_bucket=True, poison=True, stream=None):
+    def run(self, iterations=3, per_bucket=True, poison=True, stream=None, fused=False):
         w, em = self.w, self.em
         self.seed_shards()
         for it in range(iterations):
@@ -99,10 +99,11 @@ class Pair:
                     for t in em.params[p]:
                         t.fill_(float("nan"))
             torch.cuda.synchronize()
-            em.iteration(w.lr, w.momentum, per_bucket=per_bucket, stream=stream)
+            em.iteration(w.lr, w.momentum, per_bucket=per_bucket, stream=stream, fused_update=fused)
             torch.cuda.synchronize()
             self.oracle_iteration()
-            self.compare_buffer("shard_grad it%d" % it, em.shard_grad, self.sg)
+            if not fused:  # the fused kernel never writes the averaged gradient
+                self.compare_buffer("shard_grad it%d" % it, em.shard_grad, self.sg)
             self.compare_buffer("shard_mom it%d" % it, em.shard_mom, self.sm)
             self.compare_buffer("shard_param it%d" % it, em.shard_param, self.sp)
             self.compare_params("params it%d" % it)
@@ -138,6 +139,30 @@ def test_ragged_layers_all_worker_counts(P, dtype):
     pr = Pair(w)
     assert pr.em.plan.n_buckets >= 3
     pr.run(2 if P > 16 else 3, per_bucket=(P % 2 == 0))
+    pr.close()
+
+
+@pytest.mark.parametrize("P", [1, 2, 3, 4, 8, 9, 12, 64])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_fused_reduce_scatter_update(P, dtype):
+    """dear_reduce_scatter_update must leave the same bits in the parameter and momentum
+    shards as dear_reduce_scatter followed by dear_shard_update (both compared with the oracle)."""
+    say("case: fused RS+update P=%d %s" % (P, dtype))
+    g = 4 if dtype == "f32" else 2
+    w = small_workload(RAGGED + [70001, 2], P, 36000 * g, dtype, index=110 + P)
+    pr = Pair(w)
+    pr.run(3, per_bucket=(P % 2 == 1), fused=True)
+    pr.close()
+
+
+def test_fused_tiny_and_many_tiles():
+    say("case: fused RS+update, tiny config and many tiles")
+    pr = Pair(W.get_workload("tiny"))
+    pr.run(3, fused=True)
+    pr.close()
+    w = small_workload([1_000_003, 5, 65_537, 250_001, 2], 8, 1_100_000 * 2, "bf16", index=42, std=1e-3)
+    pr = Pair(w)
+    pr.run(2, fused=True)
     pr.close()
 
 
