@@ -118,7 +118,9 @@ int dear_plan_view(const dear_plan_t *plan, dear_plan_view_t *out);
  * bucket-position order; a layer run is cut at multiples of DEAR_TILE_ELEMS of the
  * layer's own element index, so only the first and last 16-byte vector of a run can be
  * partial. */
+#ifndef DEAR_TILE_ELEMS
 #define DEAR_TILE_ELEMS 4096
+#endif
 typedef struct {
     int64_t src_begin; /* first element inside the layer tensor                         */
     int64_t dst_begin; /* element offset inside a shard buffer: row*total_shard_len+...  */
@@ -227,6 +229,15 @@ int dear_reduce_scatter_update(dear_ctx_t *ctx, int32_t bucket, float *shard_par
  * Errors: DEAR_EINVAL, DEAR_ERANGE, DEAR_EALIGN, DEAR_EHIP.
  */
 int dear_all_gather(dear_ctx_t *ctx, int32_t bucket, const float *shard_param, void *hip_stream);
+
+/* dear_all_gather_workers -- dear_all_gather restricted to the workers
+ * first_worker .. first_worker+n_workers-1 (only their parameter tensors are written).
+ * With one worker it turns any shard buffer (e.g. the momentum shards) back into that
+ * worker's per-layer layout, which is what a caller needs to re-shard optimizer state
+ * when the bucket plan changes (run-time tuning of the buffer size, paper Section IV-B).
+ * Errors as dear_all_gather; DEAR_ERANGE also for a worker range outside 0 .. P-1. */
+int dear_all_gather_workers(dear_ctx_t *ctx, int32_t bucket, const float *shard_param,
+                            int32_t first_worker, int32_t n_workers, void *hip_stream);
 
 /* ---------------------------------------------------------------------------------
  * dear_scatter_params -- seed the owned parameter shards from worker `worker`'s full

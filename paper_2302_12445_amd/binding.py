@@ -23,7 +23,7 @@ EXPORTS = [
     "dear_plan", "dear_plan_fixed_layers", "dear_plan_free", "dear_plan_view", "dear_plan_tiles",
     "dear_ctx_create", "dear_ctx_destroy",
     "dear_reduce_scatter", "dear_reduce_scatter_update", "dear_shard_update", "dear_all_gather",
-    "dear_scatter_params", "dear_strerror", "dear_version",
+    "dear_all_gather_workers", "dear_scatter_params", "dear_strerror", "dear_version",
 ]
 
 
@@ -82,12 +82,14 @@ def load_library() -> C.CDLL:
     lib.dear_shard_update.argtypes = [vp, i32, vp, vp, vp, f32, f32, vp]
     lib.dear_reduce_scatter_update.argtypes = [vp, i32, vp, vp, f32, f32, vp]
     lib.dear_all_gather.argtypes = [vp, i32, vp, vp]
+    lib.dear_all_gather_workers.argtypes = [vp, i32, vp, i32, i32, vp]
     lib.dear_scatter_params.argtypes = [vp, i32, vp, vp]
     lib.dear_strerror.argtypes = [C.c_int]
     lib.dear_strerror.restype = C.c_char_p
     lib.dear_version.restype = C.c_int
     for name in ("dear_plan", "dear_plan_fixed_layers", "dear_plan_view", "dear_plan_tiles", "dear_ctx_create",
-                 "dear_reduce_scatter", "dear_reduce_scatter_update", "dear_shard_update", "dear_all_gather", "dear_scatter_params"):
+                 "dear_reduce_scatter", "dear_reduce_scatter_update", "dear_shard_update", "dear_all_gather",
+                 "dear_all_gather_workers", "dear_scatter_params"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -239,6 +241,12 @@ def dear_reduce_scatter_update(ctx: Context, bucket: int, shard_param: int, shar
 def dear_all_gather(ctx: Context, bucket: int, shard_param: int, stream: Optional[int] = None) -> None:
     _check(load_library().dear_all_gather(ctx.handle, bucket, C.c_void_p(shard_param), _stream(stream)),
            "dear_all_gather")
+
+
+def dear_all_gather_workers(ctx: Context, bucket: int, shard_param: int, first_worker: int, n_workers: int,
+                            stream: Optional[int] = None) -> None:
+    _check(load_library().dear_all_gather_workers(ctx.handle, bucket, C.c_void_p(shard_param), first_worker,
+                                                  n_workers, _stream(stream)), "dear_all_gather_workers")
 
 
 def dear_scatter_params(ctx: Context, worker: int, shard_param: int, stream: Optional[int] = None) -> None:

@@ -430,19 +430,21 @@ constexpr int AG_SPLIT = DEAR_TILE_ELEMS / (4 * DEAR_BLOCK * AG_U);
 static_assert(AG_SPLIT >= 1 && (AG_SPLIT & (AG_SPLIT - 1)) == 0, "DEAR_AG_U must divide the tile");
 constexpr int AG_CHUNK_WG = DEAR_AG_CHUNK_BYTES / (16 * DEAR_BLOCK * AG_U);  // parts per chunk
 
-// n_parts = tiles * AG_SPLIT; the grid has n_parts * P workgroups.
+// n_parts = tiles * AG_SPLIT; replicas p_first .. p_first+n_p-1 receive; the grid has
+// n_parts * n_p workgroups.
 __global__ __launch_bounds__(DEAR_BLOCK) void all_gather_kernel(
-    const dear_tile *__restrict__ tiles, float *const *__restrict__ param_tab, int L, int P,
-    const float *__restrict__ shard_param, unsigned n_parts)
+    const dear_tile *__restrict__ tiles, float *const *__restrict__ param_tab, int L, int p_first,
+    int n_p, const float *__restrict__ shard_param, unsigned n_parts)
 {
-    // blockIdx -> (chunk, replica p, part within chunk); the last chunk may be short
-    const unsigned per_chunk = AG_CHUNK_WG * (unsigned)P;
+    // blockIdx -> (chunk, replica, part within chunk); the last chunk may be short
+    const unsigned per_chunk = AG_CHUNK_WG * (unsigned)n_p;
     const unsigned chunk = blockIdx.x / per_chunk;
     const unsigned r = blockIdx.x - chunk * per_chunk;
     const unsigned first = chunk * AG_CHUNK_WG;
     const unsigned len = n_parts - first < AG_CHUNK_WG ? n_parts - first : AG_CHUNK_WG;
-    const unsigned p = r / len;
-    const unsigned id = first + (r - p * len);
+    const unsigned q = r / len;
+    const unsigned id = first + (r - q * len);
+    const unsigned p = (unsigned)p_first + q;
 
     const dear_tile t = tiles[id / AG_SPLIT];
     const int part = id % AG_SPLIT;
@@ -672,20 +674,29 @@ extern "C" int dear_shard_update(dear_ctx_t *c, int32_t bucket, const float *sha
     return launch_status();
 }
 
-extern "C" int dear_all_gather(dear_ctx_t *c, int32_t bucket, const float *shard_param, void *hip_stream)
+extern "C" int dear_all_gather_workers(dear_ctx_t *c, int32_t bucket, const float *shard_param,
+                                       int32_t first_worker, int32_t n_workers, void *hip_stream)
 {
     int rc = check_call(c, bucket);
     if (rc == DEAR_OK) rc = check_shard_buffer(shard_param);
     if (rc != DEAR_OK) return rc;
+    if (first_worker < 0 || n_workers < 1 || first_worker > c->P - n_workers) return DEAR_ERANGE;
     int64_t first, count;
     tile_range(c, bucket, first, count);
     if (count == 0) return DEAR_OK;
     const int64_t n_parts = count * AG_SPLIT;
-    if (n_parts * c->P > 0x7fffffff) return DEAR_EINVAL;
-    all_gather_kernel<<<dim3(static_cast<unsigned>(n_parts * c->P)), dim3(DEAR_BLOCK), 0,
-                        static_cast<hipStream_t>(hip_stream)>>>(c->d_tiles + first, c->d_param, c->L, c->P,
-                                                                shard_param, static_cast<unsigned>(n_parts));
+    if (n_parts * n_workers > 0x7fffffff) return DEAR_EINVAL;
+    all_gather_kernel<<<dim3(static_cast<unsigned>(n_parts * n_workers)), dim3(DEAR_BLOCK), 0,
+                        static_cast<hipStream_t>(hip_stream)>>>(c->d_tiles + first, c->d_param, c->L,
+                                                                first_worker, n_workers, shard_param,
+                                                                static_cast<unsigned>(n_parts));
     return launch_status();
+}
+
+extern "C" int dear_all_gather(dear_ctx_t *c, int32_t bucket, const float *shard_param, void *hip_stream)
+{
+    if (!c) return DEAR_EINVAL;
+    return dear_all_gather_workers(c, bucket, shard_param, 0, c->P, hip_stream);
 }
 
 extern "C" int dear_scatter_params(dear_ctx_t *c, int32_t worker, float *shard_param, void *hip_stream)

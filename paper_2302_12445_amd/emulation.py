@@ -119,5 +119,33 @@ class EmulatedWorkers:
         for b in reversed(buckets):
             self.all_gather(b, stream)
 
+    def replan(self, threshold_bytes: Optional[int] = None, plan: Optional[B.Plan] = None, stream=None) -> None:
+        """Switch to another bucket plan over the same tensors, carrying the optimizer state
+        over: parameters and momentum are re-sharded for the new plan with library calls only.
+        Expects the state after an all-gather (every replica holds the current parameters)."""
+        g = self.plan.grad_elem_bytes
+        new_plan = plan if plan is not None else B.dear_plan(self.sizes, self.P, threshold_bytes, g)
+        gp = [t.data_ptr() for rep in self.grads for t in rep]
+        wp = [t.data_ptr() for rep in self.params for t in rep]
+        with torch.cuda.device(self.device):
+            new_ctx = B.dear_ctx_create(new_plan, B.DEAR_F32 if g == 4 else B.DEAR_BF16, gp, wp)
+        row = new_plan.total_shard_len
+        new_param = torch.zeros(self.P, row, dtype=torch.float32, device=self.device)
+        new_mom = torch.zeros(self.P, row, dtype=torch.float32, device=self.device)
+        new_grad = torch.zeros(self.P, row, dtype=torch.float32, device=self.device)
+        h = _stream_handle(stream)
+        # w: worker 0's tensors -> new shards
+        B.dear_scatter_params(new_ctx, 0, new_param.data_ptr(), h)
+        # v: old shards -> worker 0's tensors (borrowed) -> new shards
+        B.dear_all_gather_workers(self.ctx, -1, self.shard_mom.data_ptr(), 0, 1, h)
+        B.dear_scatter_params(new_ctx, 0, new_mom.data_ptr(), h)
+        # give worker 0 its parameters back
+        B.dear_all_gather_workers(new_ctx, -1, new_param.data_ptr(), 0, 1, h)
+        s = stream if stream is not None else torch.cuda.current_stream()
+        s.synchronize()  # the old context and buffers are released below
+        self.ctx.destroy()
+        self.ctx, self.plan = new_ctx, new_plan
+        self.shard_grad, self.shard_param, self.shard_mom = new_grad, new_param, new_mom
+
     def close(self) -> None:
         self.ctx.destroy()

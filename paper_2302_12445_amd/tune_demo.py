@@ -1,0 +1,80 @@
+"""Buffer-size tuning demo (paper Section IV-B): Bayesian optimisation of the fusion
+threshold x against the measured iteration throughput of the one-GPU DeAR schedule,
+beside random and grid search with the same number of trials.  Prints one JSON line.
+
+    python -m paper_2302_12445_amd.tune_demo --workload resnet50 --trials 12
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+
+import torch
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def main() -> None:
+    import workloads as W
+    from paper_2302_12445_amd.emulation import EmulatedWorkers
+    from paper_2302_12445_amd.schedule import DearSchedule
+    from paper_2302_12445_amd.tuner import MB, BufferSizeTuner, grid_search, random_search
+
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--workload", default="resnet50", choices=W.WORKLOAD_NAMES)
+    ap.add_argument("--trials", type=int, default=12)
+    ap.add_argument("--steps", type=int, default=10, help="iterations averaged per trial")
+    ap.add_argument("--gemm-dim", type=int, default=2048)
+    ap.add_argument("--layers-per-gemm", type=int, default=8,
+                    help="one forward (two backward) GEMMs per this many parameter tensors")
+    ap.add_argument("--baselines", action="store_true", help="also run random and grid search")
+    args = ap.parse_args()
+    if not torch.cuda.is_available():
+        print("tune_demo needs a GPU", file=sys.stderr)
+        sys.exit(2)
+
+    device = "cuda:0"
+    w = W.get_workload(args.workload)
+    em = EmulatedWorkers(w.sizes, w.P, w.grad_dtype, 25 * MB, device)
+    param = W.make_flat_param(w, device)
+    for p in range(w.P):
+        em.load_dense(em.params[p], param)
+        em.load_dense(em.grads[p], W.make_flat_grad(w, p, 0, device))
+    em.scatter_params(0)
+    torch.cuda.synchronize()
+    n_trials = [0]
+
+    def measure(x_bytes: int) -> float:
+        """Iterations per second of the DeAR schedule with buffer size x.  The synthetic
+        compute is spread over the layers, so a plan with more buckets has finer pipelining
+        but more launches -- the trade-off the paper tunes."""
+        em.replan(int(x_bytes))
+        nb = em.plan.n_buckets
+        per_bucket = max(1, round(w.n_layers / args.layers_per_gemm / nb))
+        sched = DearSchedule(em, w.lr, w.momentum, args.gemm_dim, ff_gemms=per_bucket, bp_gemms=2 * per_bucket)
+        ms = sched.time_mode("dear", iterations=args.steps, warmup=2)
+        n_trials[0] += 1
+        return 1e3 / ms
+
+    tuner = BufferSizeTuner()
+    bx, by = tuner.run(measure, args.trials)
+    out = {"workload": w.name, "trials": args.trials, "steps_per_trial": args.steps,
+           "bo": {"best_mb": round(bx / MB, 2), "best_it_per_s": round(by, 3),
+                  "trace_mb": [round((tuner.lo + u * (tuner.hi - tuner.lo)) / MB, 1) for u in tuner.xs],
+                  "trace_it_per_s": [round(v, 3) for v in tuner.ys]},
+           "default_25mb_it_per_s": round(tuner.ys[0], 3)}
+    if args.baselines:
+        rx, ry, _ = random_search(measure, args.trials)
+        gx, gy, _ = grid_search(measure, args.trials)
+        out["random"] = {"best_mb": round(rx / MB, 2), "best_it_per_s": round(ry, 3)}
+        out["grid"] = {"best_mb": round(gx / MB, 2), "best_it_per_s": round(gy, 3)}
+    print(json.dumps(out), flush=True)
+    em.close()
+
+
+if __name__ == "__main__":
+    main()

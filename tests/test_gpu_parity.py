@@ -319,3 +319,13 @@ def test_resnet50_config_one_iteration():
     assert pr.em.plan.n_buckets == 5
     pr.run(1)
     pr.close()
+
+
+@pytest.mark.parametrize("name", ["densenet201", "inception_v4"])
+def test_many_small_tensors_full_size(name):
+    """The paper's other two CNNs at full size: 604 / 449 tensors, hundreds of them a few
+    hundred elements long, so most tiles are short runs and edge vectors."""
+    say("case: %s full size" % name)
+    pr = Pair(W.get_workload(name))
+    pr.run(1, fused=(name == "inception_v4"))
+    pr.close()

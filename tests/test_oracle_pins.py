@@ -29,7 +29,8 @@ def _rows(path):
 
 # ----------------------------------------------------------------- workloads vs Table I
 def test_shapes_match_table1():
-    gens = {"resnet50": W.resnet50_sizes, "bert_base": W.bert_base_sizes,
+    gens = {"resnet50": W.resnet50_sizes, "densenet201": W.densenet201_sizes,
+            "inception_v4": W.inception_v4_sizes, "bert_base": W.bert_base_sizes,
             "bert_large": W.bert_large_sizes}
     seen = 0
     for name, tensors, params_m in _rows(os.path.join(GOLDEN, "table1_models.txt")):
@@ -37,7 +38,7 @@ def test_shapes_match_table1():
         assert len(sizes) == int(tensors)
         assert round(sum(sizes) / 1e6, 1) == float(params_m)
         seen += 1
-    assert seen == 3
+    assert seen == 5
 
 
 # ----------------------------------------------------------------- plan: worked example

@@ -58,6 +58,72 @@ def resnet50_sizes() -> List[int]:
     return s
 
 
+def densenet201_sizes() -> List[int]:
+    """DenseNet-201 (growth rate 32, bottleneck width 4, blocks of 6/12/48/32 layers).
+
+    Table I lists 604 tensors / 20.0 M parameters for this model.
+    """
+    s: List[int] = []
+    growth, bn_size, feats = 32, 4, 64
+    s.append(64 * 3 * 7 * 7)
+    s.extend([64, 64])
+    blocks = (6, 12, 48, 32)
+    for bi, layers in enumerate(blocks):
+        for _ in range(layers):
+            s.extend([feats, feats])                          # norm1
+            s.append(bn_size * growth * feats)                # 1x1 bottleneck conv
+            s.extend([bn_size * growth, bn_size * growth])    # norm2
+            s.append(growth * bn_size * growth * 9)           # 3x3 conv
+            feats += growth
+        if bi != len(blocks) - 1:                             # transition: norm + 1x1 conv halving the width
+            s.extend([feats, feats])
+            s.append((feats // 2) * feats)
+            feats //= 2
+    s.extend([feats, feats])                                  # final norm
+    s.append(1000 * feats)
+    s.append(1000)
+    return s
+
+
+def inception_v4_sizes() -> List[int]:
+    """Inception-v4: 149 convolution + BatchNorm units (weight, BN weight, BN bias) and the
+    classifier.  Table I lists 449 tensors / 42.7 M parameters for this model."""
+    s: List[int] = []
+
+    def unit(cin, cout, kh, kw):
+        s.append(cout * cin * kh * kw)
+        s.extend([cout, cout])
+
+    # stem
+    unit(3, 32, 3, 3); unit(32, 32, 3, 3); unit(32, 64, 3, 3)
+    unit(64, 96, 3, 3)                                         # mixed 3a (beside a max-pool)
+    unit(160, 64, 1, 1); unit(64, 96, 3, 3)                    # mixed 4a, branch 0
+    unit(160, 64, 1, 1); unit(64, 64, 1, 7); unit(64, 64, 7, 1); unit(64, 96, 3, 3)
+    unit(192, 192, 3, 3)                                       # mixed 5a (beside a max-pool)
+    for _ in range(4):                                         # Inception-A, 384 channels
+        unit(384, 96, 1, 1)
+        unit(384, 64, 1, 1); unit(64, 96, 3, 3)
+        unit(384, 64, 1, 1); unit(64, 96, 3, 3); unit(96, 96, 3, 3)
+        unit(384, 96, 1, 1)
+    unit(384, 384, 3, 3)                                       # Reduction-A -> 1024 channels
+    unit(384, 192, 1, 1); unit(192, 224, 3, 3); unit(224, 256, 3, 3)
+    for _ in range(7):                                         # Inception-B
+        unit(1024, 384, 1, 1)
+        unit(1024, 192, 1, 1); unit(192, 224, 1, 7); unit(224, 256, 7, 1)
+        unit(1024, 192, 1, 1); unit(192, 192, 7, 1); unit(192, 224, 1, 7); unit(224, 224, 7, 1); unit(224, 256, 1, 7)
+        unit(1024, 128, 1, 1)
+    unit(1024, 192, 1, 1); unit(192, 192, 3, 3)                # Reduction-B -> 1536 channels
+    unit(1024, 256, 1, 1); unit(256, 256, 1, 7); unit(256, 320, 7, 1); unit(320, 320, 3, 3)
+    for _ in range(3):                                         # Inception-C
+        unit(1536, 256, 1, 1)
+        unit(1536, 384, 1, 1); unit(384, 256, 1, 3); unit(384, 256, 3, 1)
+        unit(1536, 384, 1, 1); unit(384, 448, 3, 1); unit(448, 512, 1, 3); unit(512, 256, 1, 3); unit(512, 256, 3, 1)
+        unit(1536, 256, 1, 1)
+    s.append(1000 * 1536)
+    s.append(1000)
+    return s
+
+
 def bert_sizes(layers: int, hidden: int, ffn: int, vocab: int = 30522,
                max_pos: int = 512, type_vocab: int = 2) -> List[int]:
     """BERT pre-training model (MLM + NSP heads) parameter tensors.
@@ -135,6 +201,10 @@ def get_workload(name: str) -> Workload:
         return Workload("bert_base", 2, 16, bert_base_sizes(), "f32", 1e-3, 64 * MB)
     if name == "bert_large":
         return Workload("bert_large", 3, 8, bert_large_sizes(), "bf16", 1e-3, 64 * MB)
+    if name == "densenet201":
+        return Workload("densenet201", 5, 8, densenet201_sizes(), "f32", 1e-3, 25 * MB)
+    if name == "inception_v4":
+        return Workload("inception_v4", 6, 8, inception_v4_sizes(), "f32", 1e-3, 25 * MB)
     if name == "stress_single":
         return Workload("stress_single", 4, 64, bert_base_sizes(), "f32", 1e-3, NO_LIMIT)
     if name == "stress_16mb":
@@ -142,7 +212,8 @@ def get_workload(name: str) -> Workload:
     raise KeyError(name)
 
 
-WORKLOAD_NAMES = ["tiny", "resnet50", "bert_base", "bert_large", "stress_single", "stress_16mb"]
+WORKLOAD_NAMES = ["tiny", "resnet50", "bert_base", "bert_large", "stress_single", "stress_16mb",
+                  "densenet201", "inception_v4"]
 
 
 # --------------------------------------------------------------------------- seeded inputs
