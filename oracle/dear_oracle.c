@@ -22,7 +22,7 @@
  * (build with -ffp-contract=off, no fast-math).  A "group" in the paper is a "bucket"
  * here; a "chunk" is a "shard".
  *
- * Readings where the paper is silent (all restated in the design document):
+ * Readings where the paper is silent:
  *   - a group is closed BEFORE the layer that would push it past x; a total equal to x
  *     stays in the group; a single tensor larger than x is a group of its own
  *     (tensors are never partitioned, Sec. III-B);
