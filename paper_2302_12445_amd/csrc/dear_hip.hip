@@ -36,6 +36,7 @@ typedef f4 f4_dword_aligned __attribute__((aligned(4)));  // 16-byte access, 4-b
 struct dear_ctx_impl {
     int32_t L = 0, B = 0, P = 0, g = 0;
     int device = 0;
+    int32_t max_workgroups = 0;  // 0: one workgroup per work item
     int64_t row_len = 0;
     std::vector<int64_t> bucket_shard_len, bucket_shard_base;
     std::vector<int64_t> tile_begin;  // [B+1] range of bucket b's tiles in the tile table
@@ -155,6 +156,25 @@ __device__ __forceinline__ void add_vector(float (&acc)[VE], const u4 r)
     } else {
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[j] = acc[j] + __uint_as_float(r[j]);
+    }
+}
+
+// Launch width.  By default every work item (a part of a tile, a block of update vectors)
+// gets a workgroup of its own: BOUNDED = false, the grid equals the item count and the
+// hardware's in-order workgroup dispatch paces the memory streams.  A context may bound the
+// grid (dear_ctx_set_max_workgroups): BOUNDED = true, each workgroup strides over the items.
+// That is for running beside compute kernels on the same GPU: a few hundred resident
+// workgroups with many loads in flight each disturb a GEMM's memory latency far less than
+// a full grid, and a raised wave priority keeps these few wavefronts from being starved
+// of issue slots by an MFMA-saturated neighbour.
+template <bool BOUNDED, class Body>
+__device__ __forceinline__ void for_each_item(unsigned n_items, Body body)
+{
+    if (!BOUNDED) {
+        body(blockIdx.x);
+    } else {
+        __builtin_amdgcn_s_setprio(3);
+        for (unsigned item = blockIdx.x; item < n_items; item += gridDim.x) body(item);
     }
 }
 
@@ -333,64 +353,70 @@ __device__ __forceinline__ void reduce_scatter_tile(const dear_tile &t, int part
 // Summation starts at worker s+1 and ends with worker s, the order in which the ring
 // delivers the partial sums of chunk s to its owner.  The accumulator starts as -0.0f,
 // the additive identity that keeps the first addend's bits (including a -0.0f).
-template <bool BF16, int U, int CH, bool TAIL, bool FUSED>
+template <bool BF16, int U, int CH, bool TAIL, bool FUSED, bool BOUNDED>
 __global__ __launch_bounds__(DEAR_BLOCK) void reduce_scatter_kernel(
     const dear_tile *__restrict__ tiles, const void *const *__restrict__ grad_tab, int L, int P,
-    float inv_P, const rs_sink<FUSED> o)
+    float inv_P, const rs_sink<FUSED> o, unsigned n_items)
 {
     constexpr int SPLIT = DEAR_TILE_ELEMS / ((BF16 ? 8 : 4) * DEAR_BLOCK * U);
     static_assert(SPLIT >= 1 && (SPLIT & (SPLIT - 1)) == 0, "U must divide the tile");
-    const dear_tile t = tiles[blockIdx.x / SPLIT];
-    const int part = blockIdx.x % SPLIT;
-    if (t.layer < 0) {  // padding slots: gbar = +0
-        for (int i = part * DEAR_BLOCK + threadIdx.x; i < t.count; i += SPLIT * DEAR_BLOCK)
-            emit_elem<FUSED>(o, t.dst_begin + i, 0.0f);
-        return;
-    }
-    if (t.count == DEAR_TILE_ELEMS)
-        reduce_scatter_tile<BF16, U, CH, TAIL, true, FUSED>(t, part, grad_tab, L, P, inv_P, o);
-    else
-        reduce_scatter_tile<BF16, U, CH, TAIL, false, FUSED>(t, part, grad_tab, L, P, inv_P, o);
+    for_each_item<BOUNDED>(n_items, [&](unsigned item) {
+        const dear_tile t = tiles[item / SPLIT];
+        const int part = item % SPLIT;
+        if (t.layer < 0) {  // padding slots: gbar = +0
+            for (int i = part * DEAR_BLOCK + threadIdx.x; i < t.count; i += SPLIT * DEAR_BLOCK)
+                emit_elem<FUSED>(o, t.dst_begin + i, 0.0f);
+        } else if (t.count == DEAR_TILE_ELEMS) {
+            reduce_scatter_tile<BF16, U, CH, TAIL, true, FUSED>(t, part, grad_tab, L, P, inv_P, o);
+        } else {
+            reduce_scatter_tile<BF16, U, CH, TAIL, false, FUSED>(t, part, grad_tab, L, P, inv_P, o);
+        }
+    });
 }
 
 // SGD with momentum on contiguous shard slots (paper Eq. 1-2): v = mu*v + g; w = w - lr*v.
 // blockIdx.y selects the row (worker); each row segment is `vecs` 16-byte vectors long.
-constexpr int UPD_U = DEAR_UPD_U;
+constexpr int UPD_U = DEAR_UPD_U;      // vectors per lane, one workgroup per item
+constexpr int UPD_U_BOUNDED = 4;       // bounded grid: more loads in flight per lane
+template <int U, bool BOUNDED>
 __global__ __launch_bounds__(DEAR_BLOCK) void shard_update_kernel(
     const float *__restrict__ g, float *__restrict__ w, float *__restrict__ v, int64_t row_stride,
-    int64_t base, int64_t vecs, float lr, float mu)
+    int64_t base, int64_t vecs, float lr, float mu, unsigned blocks_per_row, unsigned n_items)
 {
-    const int64_t off = (int64_t)blockIdx.y * row_stride + base;
-    const f4 *__restrict__ g4 = reinterpret_cast<const f4 *>(g + off);
-    f4 *__restrict__ w4 = reinterpret_cast<f4 *>(w + off);
-    f4 *__restrict__ v4 = reinterpret_cast<f4 *>(v + off);
-    const int64_t first = (int64_t)blockIdx.x * (UPD_U * DEAR_BLOCK) + threadIdx.x;
-    f4 gg[UPD_U], ww[UPD_U], vv[UPD_U];
+    for_each_item<BOUNDED>(n_items, [&](unsigned item) {
+        const unsigned row = item / blocks_per_row, bx = item - row * blocks_per_row;
+        const int64_t off = (int64_t)row * row_stride + base;
+        const f4 *__restrict__ g4 = reinterpret_cast<const f4 *>(g + off);
+        f4 *__restrict__ w4 = reinterpret_cast<f4 *>(w + off);
+        f4 *__restrict__ v4 = reinterpret_cast<f4 *>(v + off);
+        const int64_t first = (int64_t)bx * (U * DEAR_BLOCK) + threadIdx.x;
+        f4 gg[U], ww[U], vv[U];
 #pragma unroll
-    for (int u = 0; u < UPD_U; ++u) {
-        const int64_t i = first + u * DEAR_BLOCK;
-        if (i < vecs) {
-            gg[u] = load_vec<DEAR_UPD_NT_LOAD>(g4 + i);
-            ww[u] = load_vec<DEAR_UPD_NT_LOAD>(w4 + i);
-            vv[u] = load_vec<DEAR_UPD_NT_LOAD>(v4 + i);
-        }
-    }
-#pragma unroll
-    for (int u = 0; u < UPD_U; ++u) {
-        const int64_t i = first + u * DEAR_BLOCK;
-        if (i < vecs) {
-            f4 nv, nw;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float t1 = mu * vv[u][j];
-                nv[j] = t1 + gg[u][j];
-                const float t2 = lr * nv[j];
-                nw[j] = ww[u][j] - t2;
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = first + u * DEAR_BLOCK;
+            if (i < vecs) {
+                gg[u] = load_vec<DEAR_UPD_NT_LOAD>(g4 + i);
+                ww[u] = load_vec<DEAR_UPD_NT_LOAD>(w4 + i);
+                vv[u] = load_vec<DEAR_UPD_NT_LOAD>(v4 + i);
             }
-            store_vec<DEAR_UPD_NT_STORE>(v4 + i, nv);
-            store_vec<DEAR_UPD_NT_STORE>(w4 + i, nw);
         }
-    }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = first + u * DEAR_BLOCK;
+            if (i < vecs) {
+                f4 nv, nw;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float t1 = mu * vv[u][j];
+                    nv[j] = t1 + gg[u][j];
+                    const float t2 = lr * nv[j];
+                    nw[j] = ww[u][j] - t2;
+                }
+                store_vec<DEAR_UPD_NT_STORE>(v4 + i, nv);
+                store_vec<DEAR_UPD_NT_STORE>(w4 + i, nw);
+            }
+        }
+    });
 }
 
 // All-gather with the copy-back to the layer tensors folded in (paper Sec. III-A, IV-A).
@@ -398,8 +424,8 @@ __global__ __launch_bounds__(DEAR_BLOCK) void shard_update_kernel(
 // One workgroup copies one part of one tile to ONE replica.  Workgroups are ordered
 // (chunk, replica, part): the hardware starts workgroups in index order, so at any moment
 // the chip writes a long sequential run of one or two replicas instead of P interleaved
-// streams, which HBM sustains markedly better; the chunk's shard values (AG_CHUNK_WG
-// parts, a few MiB) are re-read for replicas 1..P-1 from L2 / Infinity Cache, not HBM.
+// streams, which HBM sustains markedly better; the chunk's shard values
+// (DEAR_AG_CHUNK_BYTES, a few MiB) are re-read for replicas 1..P-1 from L2 / Infinity Cache, not HBM.
 template <int U, bool ALL_FULL>
 __device__ __forceinline__ void all_gather_tile(const dear_tile &t, int part, DEAR_GLOBAL float *out,
                                                 const float *__restrict__ src)
@@ -425,36 +451,40 @@ __device__ __forceinline__ void all_gather_tile(const dear_tile &t, int part, DE
     }
 }
 
-constexpr int AG_U = DEAR_AG_U;
-constexpr int AG_SPLIT = DEAR_TILE_ELEMS / (4 * DEAR_BLOCK * AG_U);
-static_assert(AG_SPLIT >= 1 && (AG_SPLIT & (AG_SPLIT - 1)) == 0, "DEAR_AG_U must divide the tile");
-constexpr int AG_CHUNK_WG = DEAR_AG_CHUNK_BYTES / (16 * DEAR_BLOCK * AG_U);  // parts per chunk
+constexpr int AG_U = DEAR_AG_U;   // vectors per lane, one workgroup per item
+constexpr int AG_U_BOUNDED = 4;   // bounded grid: a whole tile per item, more loads in flight
 
-// n_parts = tiles * AG_SPLIT; replicas p_first .. p_first+n_p-1 receive; the grid has
-// n_parts * n_p workgroups.
+// n_parts = tiles * SPLIT; replicas p_first .. p_first+n_p-1 receive; there are
+// n_parts * n_p work items.
+template <int U, bool BOUNDED>
 __global__ __launch_bounds__(DEAR_BLOCK) void all_gather_kernel(
     const dear_tile *__restrict__ tiles, float *const *__restrict__ param_tab, int L, int p_first,
-    int n_p, const float *__restrict__ shard_param, unsigned n_parts)
+    int n_p, const float *__restrict__ shard_param, unsigned n_parts, unsigned n_items)
 {
-    // blockIdx -> (chunk, replica, part within chunk); the last chunk may be short
-    const unsigned per_chunk = AG_CHUNK_WG * (unsigned)n_p;
-    const unsigned chunk = blockIdx.x / per_chunk;
-    const unsigned r = blockIdx.x - chunk * per_chunk;
-    const unsigned first = chunk * AG_CHUNK_WG;
-    const unsigned len = n_parts - first < AG_CHUNK_WG ? n_parts - first : AG_CHUNK_WG;
-    const unsigned q = r / len;
-    const unsigned id = first + (r - q * len);
-    const unsigned p = (unsigned)p_first + q;
+    constexpr int SPLIT = DEAR_TILE_ELEMS / (4 * DEAR_BLOCK * U);
+    static_assert(SPLIT >= 1 && (SPLIT & (SPLIT - 1)) == 0, "U must divide the tile");
+    constexpr unsigned CHUNK = DEAR_AG_CHUNK_BYTES / (16 * DEAR_BLOCK * U);  // parts per chunk
+    const unsigned per_chunk = CHUNK * (unsigned)n_p;
+    for_each_item<BOUNDED>(n_items, [&](unsigned item) {
+        // item -> (chunk, replica, part within chunk); the last chunk may be short
+        const unsigned chunk = item / per_chunk;
+        const unsigned r = item - chunk * per_chunk;
+        const unsigned first = chunk * CHUNK;
+        const unsigned len = n_parts - first < CHUNK ? n_parts - first : CHUNK;
+        const unsigned q = r / len;
+        const unsigned id = first + (r - q * len);
+        const unsigned p = (unsigned)p_first + q;
 
-    const dear_tile t = tiles[id / AG_SPLIT];
-    const int part = id % AG_SPLIT;
-    if (t.layer < 0) return;
-    const float *__restrict__ src = shard_param + t.dst_begin;
-    DEAR_GLOBAL float *out = (DEAR_GLOBAL float *)param_tab[(size_t)p * L + t.layer];
-    if (t.count == DEAR_TILE_ELEMS)
-        all_gather_tile<AG_U, true>(t, part, out, src);
-    else
-        all_gather_tile<AG_U, false>(t, part, out, src);
+        const dear_tile t = tiles[id / SPLIT];
+        const int part = id % SPLIT;
+        if (t.layer < 0) return;
+        const float *__restrict__ src = shard_param + t.dst_begin;
+        DEAR_GLOBAL float *out = (DEAR_GLOBAL float *)param_tab[(size_t)p * L + t.layer];
+        if (t.count == DEAR_TILE_ELEMS)
+            all_gather_tile<U, true>(t, part, out, src);
+        else
+            all_gather_tile<U, false>(t, part, out, src);
+    });
 }
 
 // Inverse of the all-gather for one worker: layer tensors -> owned shard slots.
@@ -520,26 +550,46 @@ void tile_range(const dear_ctx_impl *c, int32_t bucket, int64_t &first, int64_t 
 
 int launch_status() { return hipGetLastError() == hipSuccess ? DEAR_OK : DEAR_EHIP; }
 
+unsigned grid_width(const dear_ctx_impl *c, int64_t n_items)
+{
+    if (c->max_workgroups > 0 && n_items > c->max_workgroups) return static_cast<unsigned>(c->max_workgroups);
+    return static_cast<unsigned>(n_items);
+}
+
 template <bool BF16, bool FUSED>
-void rs_launch(int P, int64_t n_tiles, hipStream_t st, const dear_tile *tiles,
-               const void *const *grad_tab, int L, const rs_sink<FUSED> &o)
+void rs_launch(const dear_ctx_impl *c, int64_t n_tiles, hipStream_t st, const dear_tile *tiles,
+               const rs_sink<FUSED> &o)
 {
     constexpr int U = BF16 ? DEAR_RS_U_BF16 : DEAR_RS_U_F32;
     constexpr int SPLIT = DEAR_TILE_ELEMS / ((BF16 ? 8 : 4) * DEAR_BLOCK * U);
-    const dim3 grid(static_cast<unsigned>(n_tiles * SPLIT)), block(DEAR_BLOCK);
+    const int P = c->P, L = c->L;
+    const void *const *grad_tab = c->d_grad;
+    const unsigned n_items = static_cast<unsigned>(n_tiles * SPLIT);
+    const dim3 grid(grid_width(c, n_items)), block(DEAR_BLOCK);
+    const bool bounded = grid.x < n_items;
     const float inv_P = 1.0f / static_cast<float>(P);
+#define RS_LAUNCH(CH, TAIL)                                                                              \
+    do {                                                                                                 \
+        if (bounded)                                                                                     \
+            reduce_scatter_kernel<BF16, U, CH, TAIL, FUSED, true><<<grid, block, 0, st>>>(              \
+                tiles, grad_tab, L, P, inv_P, o, n_items);                                               \
+        else                                                                                             \
+            reduce_scatter_kernel<BF16, U, CH, TAIL, FUSED, false><<<grid, block, 0, st>>>(             \
+                tiles, grad_tab, L, P, inv_P, o, n_items);                                               \
+    } while (0)
     // replicas per load batch: the largest of 8/4/2/1 that divides P without a tail when
     // P is small or a multiple of 4; otherwise batches of 8 with a predicated tail
     if (P % 8 == 0)
-        reduce_scatter_kernel<BF16, U, 8, false, FUSED><<<grid, block, 0, st>>>(tiles, grad_tab, L, P, inv_P, o);
+        RS_LAUNCH(8, false);
     else if (P % 4 == 0)
-        reduce_scatter_kernel<BF16, U, 4, false, FUSED><<<grid, block, 0, st>>>(tiles, grad_tab, L, P, inv_P, o);
+        RS_LAUNCH(4, false);
     else if (P == 2)
-        reduce_scatter_kernel<BF16, U, 2, false, FUSED><<<grid, block, 0, st>>>(tiles, grad_tab, L, P, inv_P, o);
+        RS_LAUNCH(2, false);
     else if (P == 1)
-        reduce_scatter_kernel<BF16, U, 1, false, FUSED><<<grid, block, 0, st>>>(tiles, grad_tab, L, P, inv_P, o);
+        RS_LAUNCH(1, false);
     else
-        reduce_scatter_kernel<BF16, U, 8, true, FUSED><<<grid, block, 0, st>>>(tiles, grad_tab, L, P, inv_P, o);
+        RS_LAUNCH(8, true);
+#undef RS_LAUNCH
 }
 
 }  // namespace
@@ -598,6 +648,13 @@ extern "C" int dear_ctx_create(const dear_plan_t *plan, int32_t grad_dtype,
     return DEAR_OK;
 }
 
+extern "C" int dear_ctx_set_max_workgroups(dear_ctx_t *c, int32_t max_workgroups)
+{
+    if (!c || max_workgroups < 0) return DEAR_EINVAL;
+    c->max_workgroups = max_workgroups;
+    return DEAR_OK;
+}
+
 extern "C" void dear_ctx_destroy(dear_ctx_t *c)
 {
     if (!c) return;
@@ -619,9 +676,9 @@ extern "C" int dear_reduce_scatter(dear_ctx_t *c, int32_t bucket, float *shard_g
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const rs_sink<false> o{shard_grad, nullptr, nullptr, 0.0f, 0.0f};
     if (c->g == 2)
-        rs_launch<true, false>(c->P, count, st, c->d_tiles + first, c->d_grad, c->L, o);
+        rs_launch<true, false>(c, count, st, c->d_tiles + first, o);
     else
-        rs_launch<false, false>(c->P, count, st, c->d_tiles + first, c->d_grad, c->L, o);
+        rs_launch<false, false>(c, count, st, c->d_tiles + first, o);
     return launch_status();
 }
 
@@ -639,9 +696,9 @@ extern "C" int dear_reduce_scatter_update(dear_ctx_t *c, int32_t bucket, float *
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const rs_sink<true> o{nullptr, shard_param, shard_mom, lr, momentum};
     if (c->g == 2)
-        rs_launch<true, true>(c->P, count, st, c->d_tiles + first, c->d_grad, c->L, o);
+        rs_launch<true, true>(c, count, st, c->d_tiles + first, o);
     else
-        rs_launch<false, true>(c->P, count, st, c->d_tiles + first, c->d_grad, c->L, o);
+        rs_launch<false, true>(c, count, st, c->d_tiles + first, o);
     return launch_status();
 }
 
@@ -664,13 +721,22 @@ extern "C" int dear_shard_update(dear_ctx_t *c, int32_t bucket, const float *sha
         rows = static_cast<unsigned>(c->P);
     }
     const int64_t vecs = elems / 4;  // shard lengths are multiples of DEAR_SHARD_ALIGN
-    const int64_t per_block = static_cast<int64_t>(UPD_U) * DEAR_BLOCK;
+    if (vecs == 0) return DEAR_OK;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const bool bounded = c->max_workgroups > 0 &&
+                         (vecs + UPD_U_BOUNDED * DEAR_BLOCK - 1) / (UPD_U_BOUNDED * DEAR_BLOCK) * rows > c->max_workgroups;
+    const int64_t per_block = static_cast<int64_t>(bounded ? UPD_U_BOUNDED : UPD_U) * DEAR_BLOCK;
     const int64_t blocks = (vecs + per_block - 1) / per_block;
-    if (blocks == 0) return DEAR_OK;
-    if (blocks > 0x7fffffff || rows > 65535u) return DEAR_EINVAL;
-    shard_update_kernel<<<dim3(static_cast<unsigned>(blocks), rows), dim3(DEAR_BLOCK), 0,
-                          static_cast<hipStream_t>(hip_stream)>>>(shard_grad, shard_param, shard_mom,
-                                                                  c->row_len, base, vecs, lr, momentum);
+    const int64_t n_items = blocks * rows;
+    if (n_items > 0x7fffffff) return DEAR_EINVAL;
+    if (bounded)
+        shard_update_kernel<UPD_U_BOUNDED, true><<<dim3(c->max_workgroups), dim3(DEAR_BLOCK), 0, st>>>(
+            shard_grad, shard_param, shard_mom, c->row_len, base, vecs, lr, momentum,
+            static_cast<unsigned>(blocks), static_cast<unsigned>(n_items));
+    else
+        shard_update_kernel<UPD_U, false><<<dim3(static_cast<unsigned>(n_items)), dim3(DEAR_BLOCK), 0, st>>>(
+            shard_grad, shard_param, shard_mom, c->row_len, base, vecs, lr, momentum,
+            static_cast<unsigned>(blocks), static_cast<unsigned>(n_items));
     return launch_status();
 }
 
@@ -684,12 +750,21 @@ extern "C" int dear_all_gather_workers(dear_ctx_t *c, int32_t bucket, const floa
     int64_t first, count;
     tile_range(c, bucket, first, count);
     if (count == 0) return DEAR_OK;
-    const int64_t n_parts = count * AG_SPLIT;
-    if (n_parts * n_workers > 0x7fffffff) return DEAR_EINVAL;
-    all_gather_kernel<<<dim3(static_cast<unsigned>(n_parts * n_workers)), dim3(DEAR_BLOCK), 0,
-                        static_cast<hipStream_t>(hip_stream)>>>(c->d_tiles + first, c->d_param, c->L,
-                                                                first_worker, n_workers, shard_param,
-                                                                static_cast<unsigned>(n_parts));
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    constexpr int64_t split_bounded = DEAR_TILE_ELEMS / (4 * DEAR_BLOCK * AG_U_BOUNDED);
+    constexpr int64_t split_free = DEAR_TILE_ELEMS / (4 * DEAR_BLOCK * AG_U);
+    if (count * split_free * n_workers > 0x7fffffff) return DEAR_EINVAL;
+    if (c->max_workgroups > 0 && count * split_bounded * n_workers > c->max_workgroups) {
+        const int64_t n_parts = count * split_bounded, n_items = n_parts * n_workers;
+        all_gather_kernel<AG_U_BOUNDED, true><<<dim3(c->max_workgroups), dim3(DEAR_BLOCK), 0, st>>>(
+            c->d_tiles + first, c->d_param, c->L, first_worker, n_workers, shard_param,
+            static_cast<unsigned>(n_parts), static_cast<unsigned>(n_items));
+    } else {
+        const int64_t n_parts = count * split_free, n_items = n_parts * n_workers;
+        all_gather_kernel<AG_U, false><<<dim3(static_cast<unsigned>(n_items)), dim3(DEAR_BLOCK), 0, st>>>(
+            c->d_tiles + first, c->d_param, c->L, first_worker, n_workers, shard_param,
+            static_cast<unsigned>(n_parts), static_cast<unsigned>(n_items));
+    }
     return launch_status();
 }
 

@@ -145,7 +145,13 @@ class EmulatedWorkers:
         s.synchronize()  # the old context and buffers are released below
         self.ctx.destroy()
         self.ctx, self.plan = new_ctx, new_plan
+        B.dear_ctx_set_max_workgroups(self.ctx, getattr(self, "max_workgroups", 0))
         self.shard_grad, self.shard_param, self.shard_mom = new_grad, new_param, new_mom
+
+    def set_max_workgroups(self, n: int) -> None:
+        """0: one workgroup per work item (default); n > 0: bounded grid for running beside compute."""
+        self.max_workgroups = n
+        B.dear_ctx_set_max_workgroups(self.ctx, n)
 
     def close(self) -> None:
         self.ctx.destroy()

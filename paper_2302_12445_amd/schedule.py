@@ -31,10 +31,19 @@ class DearSchedule:
 
     def __init__(self, em: EmulatedWorkers, lr: float, momentum: float, gemm_dim: int = 4096,
                  ff_gemms: int = 1, bp_gemms: int = 2,
-                 on_backward: Optional[Callable[[int, int], None]] = None):
+                 on_backward: Optional[Callable[[int, int], None]] = None,
+                 overlap_workgroups: int = 256, overlap_workgroups_ag: Optional[int] = 512):
         """on_backward(iteration, bucket) runs on the compute stream behind the bucket's
-        backward GEMMs; tests use it to write that bucket's fresh gradients."""
+        backward GEMMs; tests use it to write that bucket's fresh gradients.
+        overlap_workgroups bounds the grid of the aggregation kernels in the overlapping
+        modes (dear, wfbp); 0 leaves them unbounded.  overlap_workgroups_ag, if given, is
+        the bound for the all-gather (the forward pass it hides under is half as long as
+        the backward pass, so it may need a wider grid)."""
         self.em, self.lr, self.momentum = em, lr, momentum
+        self.overlap_workgroups = overlap_workgroups
+        self.overlap_workgroups_ag = overlap_workgroups if overlap_workgroups_ag is None else overlap_workgroups_ag
+        if overlap_workgroups == 0:
+            self.overlap_workgroups_ag = 0
         self.nb = em.plan.n_buckets
         self.ff_gemms, self.bp_gemms = ff_gemms, bp_gemms
         self.on_backward = on_backward
@@ -84,6 +93,10 @@ class DearSchedule:
     # -------------------------------------------------------------- one iteration
     def iteration(self, mode: str = "dear") -> None:
         em, nb = self.em, self.nb
+        overlapping = mode in ("dear", "wfbp")
+        w_rs = self.overlap_workgroups if overlapping else 0
+        w_ag = self.overlap_workgroups_ag if overlapping else 0
+        em.set_max_workgroups(w_rs)
         if mode == "compute_only":
             self._forward(False)
             self._backward(False)
@@ -109,8 +122,10 @@ class DearSchedule:
             self._backward(True)
             for b in range(nb):
                 self.comm.wait_event(self.grad_ready[b])
+                em.set_max_workgroups(w_rs)
                 self._reduce_scatter_and_update(b, self.comm)
                 self.rs_done[b].record(self.comm)
+                em.set_max_workgroups(w_ag)
                 em.all_gather(b, self.comm)
             self.ag_done[nb - 1].record(self.comm)
             for b in range(nb - 1):
@@ -128,6 +143,7 @@ class DearSchedule:
                 self.rs_done[b].record(self.comm)
             # all OP1 precede every OP2: in order on the one communication stream.
             # OP2 in forward order, to be hidden under the next forward pass
+            em.set_max_workgroups(w_ag)
             for b in reversed(range(nb)):
                 em.all_gather(b, self.comm)
                 self.ag_done[b].record(self.comm)

@@ -33,6 +33,10 @@ def main() -> None:
     ap.add_argument("--ff-gemms", type=int, default=1, help="forward GEMMs per bucket")
     ap.add_argument("--bp-gemms", type=int, default=2, help="backward GEMMs per bucket")
     ap.add_argument("--iterations", type=int, default=10)
+    ap.add_argument("--overlap-workgroups", type=int, default=256,
+                    help="grid bound of reduce-scatter/update while they overlap compute (0 = unbounded)")
+    ap.add_argument("--overlap-workgroups-ag", type=int, default=512,
+                    help="grid bound of the all-gather while it overlaps compute")
     ap.add_argument("--trace-iterations", type=int, default=0,
                     help="after the report, run this many DeAR iterations only (for a kernel trace)")
     args = ap.parse_args()
@@ -50,11 +54,13 @@ def main() -> None:
     em.scatter_params(0)
     torch.cuda.synchronize()
 
-    sched = DearSchedule(em, w.lr, w.momentum, args.gemm_dim, args.ff_gemms, args.bp_gemms)
+    sched = DearSchedule(em, w.lr, w.momentum, args.gemm_dim, args.ff_gemms, args.bp_gemms,
+                         overlap_workgroups=args.overlap_workgroups,
+                         overlap_workgroups_ag=args.overlap_workgroups_ag)
     rep = overlap_report(sched, args.iterations)
     rep["config"] = {"workload": w.name, "P": w.P, "buckets": em.plan.n_buckets, "gemm_dim": args.gemm_dim,
                      "ff_gemms_per_bucket": args.ff_gemms, "bp_gemms_per_bucket": args.bp_gemms,
-                     "gemm_dtype": "f32"}
+                     "gemm_dtype": "f32", "overlap_workgroups": [args.overlap_workgroups, args.overlap_workgroups_ag]}
     print(json.dumps(rep), flush=True)
     for _ in range(args.trace_iterations):
         sched.iteration("dear")

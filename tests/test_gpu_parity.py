@@ -88,8 +88,9 @@ class Pair:
         oracle.shard_update(self.op, -1, self.sg, self.sp, self.sm, w.lr, w.momentum)
         oracle.all_gather(self.op, -1, self.sp, self.params)
 
-    def run(self, iterations=3, per_bucket=True, poison=True, stream=None, fused=False):
+    def run(self, iterations=3, per_bucket=True, poison=True, stream=None, fused=False, width=0):
         w, em = self.w, self.em
+        em.set_max_workgroups(width)
         self.seed_shards()
         for it in range(iterations):
             self.load_grads(it)
@@ -152,6 +153,18 @@ def test_fused_reduce_scatter_update(P, dtype):
     w = small_workload(RAGGED + [70001, 2], P, 36000 * g, dtype, index=110 + P)
     pr = Pair(w)
     pr.run(3, per_bucket=(P % 2 == 1), fused=True)
+    pr.close()
+
+
+@pytest.mark.parametrize("width", [1, 3, 64, 256])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_bounded_grid_gives_the_same_bits(width, dtype):
+    """A bounded grid (workgroups striding over the work items) is only a launch shape."""
+    say("case: bounded grid width=%d %s" % (width, dtype))
+    g = 4 if dtype == "f32" else 2
+    w = small_workload(RAGGED + [300_001], 4, 40000 * g, dtype, index=120 + width)
+    pr = Pair(w)
+    pr.run(2, per_bucket=(width != 3), fused=(width == 64), width=width)
     pr.close()
 
 

@@ -46,7 +46,8 @@ def test_schedule_matches_oracle(mode):
     em.scatter_params(0)
     torch.cuda.synchronize()
 
-    sched = DearSchedule(em, w.lr, w.momentum, gemm_dim=512, ff_gemms=1, bp_gemms=2, on_backward=on_backward)
+    sched = DearSchedule(em, w.lr, w.momentum, gemm_dim=512, ff_gemms=1, bp_gemms=2, on_backward=on_backward,
+                         overlap_workgroups=8)
     for it in range(iters):
         sched.iteration(mode)
     sched.synchronize()
