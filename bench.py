@@ -45,7 +45,7 @@ def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="bert_large", choices=W.WORKLOAD_NAMES)
     ap.add_argument("--launch", default="per_bucket", choices=["per_bucket", "all_buckets"],
                     help="one launch per bucket and phase (the DeAR schedule) or one per phase")
@@ -53,7 +53,7 @@ def parse_args():
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (torch) so that a counter "
                          "profile of this command holds a dispatch of known traffic")
-    ap.add_argument("--sample-buckets", type=int, default=2,
+    ap.add_argument("--sample-buckets", type=int, default=11,
                     help="buckets (from bucket 0) the CPU oracle is timed on")
     return ap.parse_args()
 
@@ -68,63 +68,100 @@ def fill_inputs(em, w, device):
     torch.cuda.synchronize()
 
 
-def cpu_baseline_and_check(em, w, n_buckets):
-    """Time the oracle (single thread, as it stands) on the first n_buckets buckets of the
-    workload and compare the GPU's first iteration with it there."""
-    import numpy as np
-    import oracle
+class CpuBaseline:
+    """The oracle on a bounded sample of the workload (the first n_buckets buckets, all P
+    replicas): snapshot() copies the sample's inputs to the host and runs the GPU's first
+    iteration, keeping its results; run() times the oracle (single thread, as it stands, and
+    split over host threads) after the GPU timing is done and compares the two."""
 
-    op = oracle.plan(w.sizes, w.P, w.threshold_bytes, w.grad_elem_bytes)
-    buckets = list(range(min(n_buckets, op.n_buckets)))
-    layers = [l for b in buckets
-              for l in range(int(op.bucket_first_layer[b]), int(op.bucket_first_layer[b]) + int(op.bucket_n_layers[b]))]
+    def __init__(self, em, w, n_buckets):
+        import numpy as np
+        import oracle
+        self.np, self.oracle, self.em, self.w = np, oracle, em, w
+        self.op = oracle.plan(w.sizes, w.P, w.threshold_bytes, w.grad_elem_bytes)
+        op = self.op
+        self.buckets = list(range(min(n_buckets, op.n_buckets)))
+        self.layers = [l for b in self.buckets
+                       for l in range(int(op.bucket_first_layer[b]),
+                                      int(op.bucket_first_layer[b]) + int(op.bucket_n_layers[b]))]
 
-    def host(t):
+    def host(self, t):
+        np = self.np
         t = t.cpu().contiguous()
         return t.view(torch.int16).numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.numpy()
 
-    grads = [[None] * w.n_layers for _ in range(w.P)]
-    params = [[None] * w.n_layers for _ in range(w.P)]
-    for p in range(w.P):
-        for l in layers:
-            grads[p][l] = host(em.grads[p][l])
-            params[p][l] = host(em.params[p][l]).copy()
-    row = op.total_shard_len
-    sg = np.zeros((w.P, row), np.float32)
-    sp = np.zeros_like(sg)
-    sm = np.zeros_like(sg)
-    for b in buckets:
-        oracle.scatter_params(op, params, 0, sp, bucket=b)
+    def snapshot(self):
+        em, w, op = self.em, self.w, self.op
+        self.grads = [[None] * w.n_layers for _ in range(w.P)]
+        self.params = [[None] * w.n_layers for _ in range(w.P)]
+        for p in range(w.P):
+            for l in self.layers:
+                self.grads[p][l] = self.host(em.grads[p][l])
+                self.params[p][l] = self.host(em.params[p][l]).copy()
+        # GPU: first iteration from the same state; keep what will be compared
+        em.iteration(w.lr, w.momentum, per_bucket=True)
+        torch.cuda.synchronize()
+        self.gpu_shards = {}
+        for b in self.buckets:
+            lo, S = int(op.bucket_shard_base[b]), int(op.bucket_shard_len[b])
+            self.gpu_shards[b] = [dev[:, lo:lo + S].cpu().numpy() for dev in (em.shard_grad, em.shard_param, em.shard_mom)]
+        self.gpu_params = {(p, l): self.host(em.params[p][l]).copy() for p in (0, w.P - 1) for l in self.layers}
 
-    n_sample = int(sum(op.bucket_len[b] for b in buckets))
-    t0 = time.perf_counter()
-    for b in buckets:
-        oracle.reduce_scatter(op, b, grads, sg)
-    for b in buckets:
-        oracle.shard_update(op, b, sg, sp, sm, w.lr, w.momentum)
-    for b in reversed(buckets):
-        oracle.all_gather(op, b, sp, params)
-    dt = time.perf_counter() - t0
-    sample_bytes = n_sample * (w.grad_elem_bytes * w.P + 4 * w.P + 28)
+    def run(self):
+        np, oracle, w, op = self.np, self.oracle, self.w, self.op
+        buckets, grads, params = self.buckets, self.grads, self.params
+        row = op.total_shard_len
+        sg = np.zeros((w.P, row), np.float32)
+        sp = np.zeros_like(sg)
+        sm = np.zeros_like(sg)
+        for b in buckets:
+            oracle.scatter_params(op, params, 0, sp, bucket=b)
+        n_sample = int(sum(op.bucket_len[b] for b in buckets))
+        sample_bytes = n_sample * (w.grad_elem_bytes * w.P + 4 * w.P + 28)
 
-    # GPU: first iteration from the same state, then compare on the sample
-    em.iteration(w.lr, w.momentum, per_bucket=True)
-    torch.cuda.synchronize()
-    ok = True
-    for b in buckets:
-        lo, S = int(op.bucket_shard_base[b]), int(op.bucket_shard_len[b])
-        for dev, ref in ((em.shard_grad, sg), (em.shard_param, sp), (em.shard_mom, sm)):
-            got = dev[:, lo:lo + S].cpu().numpy()
-            ok = ok and np.array_equal(got.view(np.uint32), ref[:, lo:lo + S].view(np.uint32))
-    for p in (0, w.P - 1):
-        for l in layers:
-            ok = ok and np.array_equal(host(em.params[p][l]).view(np.uint32), params[p][l].view(np.uint32))
-    return {
-        "value": round(sample_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
-        "sample": "buckets %s of %s (%d of %d elements, all %d workers), one iteration, %.1f s" % (
-            buckets, w.name, n_sample, w.N, w.P, dt),
-        "gpu_matches_oracle_on_sample": bool(ok),
-    }
+        # the same oracle calls split by shard / receiving worker over host threads (independent
+        # work, identical bits): timed first, on scratch copies, as the all-core figure
+        from concurrent.futures import ThreadPoolExecutor
+        cores = max(1, min(w.P, os.cpu_count() or 1, 16))
+        sg2, sp2, sm2 = sg.copy(), sp.copy(), sm.copy()
+        params2 = [[None if a is None else a.copy() for a in r] for r in params]
+        with ThreadPoolExecutor(cores) as ex:
+            t0 = time.perf_counter()
+            for b in buckets:
+                list(ex.map(lambda s: oracle.reduce_scatter(op, b, grads, sg2, shards=range(s, s + 1)), range(w.P)))
+            for b in buckets:
+                list(ex.map(lambda s: oracle.shard_update(op, b, sg2, sp2, sm2, w.lr, w.momentum,
+                                                          shards=range(s, s + 1)), range(w.P)))
+            for b in reversed(buckets):
+                list(ex.map(lambda p: oracle.all_gather(op, b, sp2, params2, workers=range(p, p + 1)), range(w.P)))
+            dt_all = time.perf_counter() - t0
+        del params2
+
+        t0 = time.perf_counter()
+        for b in buckets:
+            oracle.reduce_scatter(op, b, grads, sg)
+        for b in buckets:
+            oracle.shard_update(op, b, sg, sp, sm, w.lr, w.momentum)
+        for b in reversed(buckets):
+            oracle.all_gather(op, b, sp, params)
+        dt = time.perf_counter() - t0
+        threads_agree = bool(np.array_equal(sp.view(np.uint32), sp2.view(np.uint32)))
+
+        ok = True
+        for b in buckets:
+            lo, S = int(op.bucket_shard_base[b]), int(op.bucket_shard_len[b])
+            for got, ref in zip(self.gpu_shards[b], (sg, sp, sm)):
+                ok = ok and np.array_equal(got.view(np.uint32), ref[:, lo:lo + S].view(np.uint32))
+        for (p, l), got in self.gpu_params.items():
+            ok = ok and np.array_equal(got.view(np.uint32), params[p][l].view(np.uint32))
+        return {
+            "value": round(sample_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "buckets %d..%d of %s (%d of %d elements, all %d workers), one iteration, %.1f s" % (
+                buckets[0], buckets[-1], w.name, n_sample, w.N, w.P, dt),
+            "gpu_matches_oracle_on_sample": bool(ok),
+            "all_cores": {"value": round(sample_bytes / dt_all / 1e9, 3), "unit": "GB/s", "cores": cores,
+                          "same_bits_as_single_thread": threads_agree},
+        }
 
 
 def main():
@@ -147,9 +184,10 @@ def main():
     nb = em.plan.n_buckets
     per_bucket = args.launch == "per_bucket"
 
-    cpu = None
+    baseline = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline_and_check(em, w, args.sample_buckets)
+        baseline = CpuBaseline(em, w, args.sample_buckets)
+        baseline.snapshot()
 
     if args.pmc_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=device)
@@ -250,8 +288,8 @@ def main():
         "phases": {"rs_update": {"ms": round(f_rs, 4), "GBps": round(fused_rs_bytes / (f_rs * 1e-3) / 1e9, 1)},
                    "ag": {"ms": round(f_ag, 4), "GBps": round(bytes_["ag"] / (f_ag * 1e-3) / 1e9, 1)}},
     }
-    if cpu is not None:
-        line["cpu_baseline"] = cpu
+    if baseline is not None:  # the CPU leg runs after every GPU timing
+        line["cpu_baseline"] = baseline.run()
     print(json.dumps(line), flush=True)
     em.close()
 

@@ -435,13 +435,21 @@ __device__ __forceinline__ void all_gather_tile(const dear_tile &t, int part, DE
     const int64_t a = t.src_begin, c = a + t.count;
     const int64_t v_first = a / VE + (int64_t)part * (U * DEAR_BLOCK);
     if (!ALL_FULL && v_first * VE >= c) return;
+    int64_t vi[U];
+    bool full[U];
+    f4 val[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {  // all loads first, so they are in flight together
+        vi[u] = v_first + u * DEAR_BLOCK + tid;
+        const int64_t e0 = vi[u] * VE;
+        full[u] = ALL_FULL || (e0 >= a && e0 + VE <= c);
+        if (full[u]) val[u] = load_f4_dword_aligned<DEAR_AG_NT_LOAD>(src + (e0 - a));
+    }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const int64_t vi = v_first + u * DEAR_BLOCK + tid;
-        const int64_t e0 = vi * VE;
-        if (ALL_FULL || (e0 >= a && e0 + VE <= c)) {
-            const f4 val = load_f4_dword_aligned<DEAR_AG_NT_LOAD>(src + (e0 - a));
-            store_vec<DEAR_AG_NT_STORE>((global_f4_out)out + vi, val);
+        const int64_t e0 = vi[u] * VE;
+        if (full[u]) {
+            store_vec<DEAR_AG_NT_STORE>((global_f4_out)out + vi[u], val[u]);
         } else if (e0 < c) {
             for (int j = 0; j < VE; ++j) {
                 const int64_t e = e0 + j;
