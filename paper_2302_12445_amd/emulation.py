@@ -148,6 +148,20 @@ class EmulatedWorkers:
         B.dear_ctx_set_max_workgroups(self.ctx, getattr(self, "max_workgroups", 0))
         self.shard_grad, self.shard_param, self.shard_mom = new_grad, new_param, new_mom
 
+    def capture_iteration(self, lr: float, momentum: float, per_bucket: bool = True,
+                          fused_update: bool = False) -> "torch.cuda.CUDAGraph":
+        """Record one iteration (all its launches) into a HIP graph and return it; replay()
+        then runs the iteration with one submission, which matters when the step is
+        launch-bound (many small buckets).  Nothing is executed by the capture itself.  The
+        library's launches contain no memset nodes and allocate nothing, so they are safe to
+        capture; the graph is bound to this context's tensors and launch width."""
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream(device=self.device)
+        side.wait_stream(torch.cuda.current_stream(self.device))
+        with torch.cuda.graph(graph, stream=side):
+            self.iteration(lr, momentum, per_bucket=per_bucket, fused_update=fused_update)
+        return graph
+
     def set_max_workgroups(self, n: int) -> None:
         """0: one workgroup per work item (default); n > 0: bounded grid for running beside compute."""
         self.max_workgroups = n

@@ -141,3 +141,44 @@ def test_all_gather_workers_range_errors_and_subset():
     for first, n in ((-1, 1), (0, 0), (0, 5), (3, 2), (4, 1)):
         assert lib.dear_all_gather_workers(em.ctx.handle, -1, sp, first, n, None) == binding.DEAR_ERANGE
     em.close()
+
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_graph_replays_match_eager_oracle(fused):
+    """One iteration captured into a HIP graph: every replay, with eager work (fresh
+    gradients, a synchronisation) between replays, must equal the oracle's iteration."""
+    from paper_2302_12445_amd.emulation import EmulatedWorkers
+    print("case: graph capture, fused =", fused, flush=True)
+    w = W.get_workload("tiny")
+    em = EmulatedWorkers(w.sizes, w.P, w.grad_dtype, w.threshold_bytes, DEV)
+    op = oracle.plan(w.sizes, w.P, w.threshold_bytes, 4)
+    param = W.make_flat_param(w)
+    params = [split_np(to_numpy(param).copy(), w.sizes) for _ in range(w.P)]
+    for p in range(w.P):
+        em.load_dense(em.params[p], param.to(DEV))
+    em.scatter_params(0)
+    sg = np.zeros((w.P, op.total_shard_len), np.float32)
+    sp, sm = np.zeros_like(sg), np.zeros_like(sg)
+    oracle.scatter_params(op, params, 0, sp)
+    torch.cuda.synchronize()
+    graph = em.capture_iteration(w.lr, w.momentum, fused_update=fused)
+    # the capture must not have executed anything
+    assert np.array_equal(em.shard_param.cpu().numpy().view(np.uint32), sp.view(np.uint32))
+    for it in range(4):
+        flats = [W.make_flat_grad(w, p, it) for p in range(w.P)]
+        for p in range(w.P):
+            em.load_dense(em.grads[p], flats[p].to(DEV))       # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        grads = [split_np(to_numpy(f), w.sizes) for f in flats]
+        oracle.reduce_scatter(op, -1, grads, sg)
+        oracle.shard_update(op, -1, sg, sp, sm, w.lr, w.momentum)
+        oracle.all_gather(op, -1, sp, params)
+        assert np.array_equal(em.shard_param.cpu().numpy().view(np.uint32), sp.view(np.uint32)), it
+        assert np.array_equal(em.shard_mom.cpu().numpy().view(np.uint32), sm.view(np.uint32)), it
+        for p in range(w.P):
+            got = em.dense(em.params[p]).cpu().numpy()
+            assert np.array_equal(got.view(np.uint32), np.concatenate(params[p]).view(np.uint32)), (it, p)
+    del graph
+    em.close()
