@@ -153,7 +153,9 @@ int dear_plan_tiles(const dear_plan_t *plan, dear_tile_t *out, int64_t capacity,
  * pointer arrays are copied; the tensors themselves stay owned by the caller and must
  * outlive the context.  The context copies what it needs from the plan, so the plan
  * may be freed first.  Allocates device memory for its tables (pointer tables and a
- * tile table of 32 bytes per DEAR_TILE_ELEMS elements).  Uses the current HIP device.
+ * tile table of 32 bytes per DEAR_TILE_ELEMS elements).  Uses the current HIP device;
+ * every later call on the context must be made with that device current (DEAR_EINVAL
+ * otherwise).
  * Errors: DEAR_EINVAL, DEAR_EALIGN, DEAR_ENOMEM, DEAR_EHIP.
  */
 int dear_ctx_create(const dear_plan_t *plan, int32_t grad_dtype,

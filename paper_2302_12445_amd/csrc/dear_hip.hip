@@ -257,7 +257,7 @@ __device__ __forceinline__ void reduce_scatter_tile(const dear_tile &t, int part
     bool full[U];
     int64_t piece_idx[U][PIECES];  // shard-buffer element index of each result piece
     float acc[U][VE];
-    f4 w_old[U][PIECES], v_old[U][PIECES];
+    f4 w_old[U][PIECES] = {}, v_old[U][PIECES] = {};  // only the fused sink reads them
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         vi[u] = v_first + u * DEAR_BLOCK + tid;
@@ -535,6 +535,9 @@ int check_call(const dear_ctx_impl *c, int32_t bucket)
 {
     if (!c) return DEAR_EINVAL;
     if (bucket < -1 || bucket >= c->B) return DEAR_ERANGE;
+    int dev = -1;  // the tables live on the device that was current at dear_ctx_create
+    if (hipGetDevice(&dev) != hipSuccess) return DEAR_EHIP;
+    if (dev != c->device) return DEAR_EINVAL;
     return DEAR_OK;
 }
 
@@ -784,9 +787,10 @@ extern "C" int dear_all_gather(dear_ctx_t *c, int32_t bucket, const float *shard
 
 extern "C" int dear_scatter_params(dear_ctx_t *c, int32_t worker, float *shard_param, void *hip_stream)
 {
-    if (!c) return DEAR_EINVAL;
+    int rc = check_call(c, -1);
+    if (rc != DEAR_OK) return rc;
     if (worker < 0 || worker >= c->P) return DEAR_ERANGE;
-    int rc = check_shard_buffer(shard_param);
+    rc = check_shard_buffer(shard_param);
     if (rc != DEAR_OK) return rc;
     const int64_t count = c->tile_begin[c->B];
     if (count == 0) return DEAR_OK;
