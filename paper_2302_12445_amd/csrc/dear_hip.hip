@@ -460,7 +460,6 @@ __device__ __forceinline__ void all_gather_tile(const dear_tile &t, int part, DE
 }
 
 constexpr int AG_U = DEAR_AG_U;   // vectors per lane, one workgroup per item
-constexpr int AG_U_BOUNDED = 4;   // bounded grid: a whole tile per item, more loads in flight
 
 // n_parts = tiles * SPLIT; replicas p_first .. p_first+n_p-1 receive; there are
 // n_parts * n_p work items.
@@ -492,6 +491,62 @@ __global__ __launch_bounds__(DEAR_BLOCK) void all_gather_kernel(
             all_gather_tile<U, true>(t, part, out, src);
         else
             all_gather_tile<U, false>(t, part, out, src);
+    });
+}
+
+// Bounded-grid form of the all-gather: one item is a whole tile, read once and stored to all
+// receiving replicas by the same workgroup.  Beside a GEMM the grid is too narrow to be
+// bandwidth-bound, so what counts is bytes in flight per workgroup (4 loads, then 4 stores
+// per replica), not the replica-sequential order of the full-grid kernel.
+template <bool ALL_FULL>
+__device__ __forceinline__ void all_gather_tile_all_replicas(const dear_tile &t,
+                                                             float *const *__restrict__ param_tab, int L,
+                                                             int p_first, int n_p,
+                                                             const float *__restrict__ src)
+{
+    constexpr int VE = 4, U = DEAR_TILE_ELEMS / (VE * DEAR_BLOCK);
+    const int tid = threadIdx.x;
+    const int64_t a = t.src_begin, c = a + t.count;
+    const int64_t v_first = a / VE;
+    int64_t vi[U];
+    bool full[U];
+    f4 val[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        vi[u] = v_first + u * DEAR_BLOCK + tid;
+        const int64_t e0 = vi[u] * VE;
+        full[u] = ALL_FULL || (e0 >= a && e0 + VE <= c);
+        if (full[u]) val[u] = load_f4_dword_aligned<DEAR_AG_NT_LOAD>(src + (e0 - a));
+    }
+    for (int q = 0; q < n_p; ++q) {
+        DEAR_GLOBAL float *out = (DEAR_GLOBAL float *)param_tab[(size_t)(p_first + q) * L + t.layer];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t e0 = vi[u] * VE;
+            if (full[u]) {
+                store_vec<DEAR_AG_NT_STORE>((global_f4_out)out + vi[u], val[u]);
+            } else if (e0 < c) {
+                for (int j = 0; j < VE; ++j) {
+                    const int64_t e = e0 + j;
+                    if (e >= a && e < c) out[e] = src[e - a];
+                }
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(DEAR_BLOCK) void all_gather_bounded_kernel(
+    const dear_tile *__restrict__ tiles, float *const *__restrict__ param_tab, int L, int p_first,
+    int n_p, const float *__restrict__ shard_param, unsigned n_tiles)
+{
+    for_each_item<true>(n_tiles, [&](unsigned item) {
+        const dear_tile t = tiles[item];
+        if (t.layer < 0) return;
+        const float *__restrict__ src = shard_param + t.dst_begin;
+        if (t.count == DEAR_TILE_ELEMS)
+            all_gather_tile_all_replicas<true>(t, param_tab, L, p_first, n_p, src);
+        else
+            all_gather_tile_all_replicas<false>(t, param_tab, L, p_first, n_p, src);
     });
 }
 
@@ -762,14 +817,12 @@ extern "C" int dear_all_gather_workers(dear_ctx_t *c, int32_t bucket, const floa
     tile_range(c, bucket, first, count);
     if (count == 0) return DEAR_OK;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    constexpr int64_t split_bounded = DEAR_TILE_ELEMS / (4 * DEAR_BLOCK * AG_U_BOUNDED);
     constexpr int64_t split_free = DEAR_TILE_ELEMS / (4 * DEAR_BLOCK * AG_U);
     if (count * split_free * n_workers > 0x7fffffff) return DEAR_EINVAL;
-    if (c->max_workgroups > 0 && count * split_bounded * n_workers > c->max_workgroups) {
-        const int64_t n_parts = count * split_bounded, n_items = n_parts * n_workers;
-        all_gather_kernel<AG_U_BOUNDED, true><<<dim3(c->max_workgroups), dim3(DEAR_BLOCK), 0, st>>>(
+    if (c->max_workgroups > 0 && count > c->max_workgroups) {
+        all_gather_bounded_kernel<<<dim3(c->max_workgroups), dim3(DEAR_BLOCK), 0, st>>>(
             c->d_tiles + first, c->d_param, c->L, first_worker, n_workers, shard_param,
-            static_cast<unsigned>(n_parts), static_cast<unsigned>(n_items));
+            static_cast<unsigned>(count));
     } else {
         const int64_t n_parts = count * split_free, n_items = n_parts * n_workers;
         all_gather_kernel<AG_U, false><<<dim3(static_cast<unsigned>(n_items)), dim3(DEAR_BLOCK), 0, st>>>(

@@ -32,7 +32,7 @@ class DearSchedule:
     def __init__(self, em: EmulatedWorkers, lr: float, momentum: float, gemm_dim: int = 4096,
                  ff_gemms: int = 1, bp_gemms: int = 2,
                  on_backward: Optional[Callable[[int, int], None]] = None,
-                 overlap_workgroups: int = 256, overlap_workgroups_ag: Optional[int] = 512):
+                 overlap_workgroups: int = 256, overlap_workgroups_ag: Optional[int] = 192):
         """on_backward(iteration, bucket) runs on the compute stream behind the bucket's
         backward GEMMs; tests use it to write that bucket's fresh gradients.
         overlap_workgroups bounds the grid of the aggregation kernels in the overlapping

@@ -35,7 +35,7 @@ def main() -> None:
     ap.add_argument("--iterations", type=int, default=10)
     ap.add_argument("--overlap-workgroups", type=int, default=256,
                     help="grid bound of reduce-scatter/update while they overlap compute (0 = unbounded)")
-    ap.add_argument("--overlap-workgroups-ag", type=int, default=512,
+    ap.add_argument("--overlap-workgroups-ag", type=int, default=192,
                     help="grid bound of the all-gather while it overlaps compute")
     ap.add_argument("--trace-iterations", type=int, default=0,
                     help="after the report, run this many DeAR iterations only (for a kernel trace)")
