@@ -342,3 +342,29 @@ def test_many_small_tensors_full_size(name):
     pr = Pair(W.get_workload(name))
     pr.run(1, fused=(name == "inception_v4"))
     pr.close()
+
+
+def test_random_configurations():
+    """Seeded random layer lists, worker counts, thresholds, gradient types, launch widths,
+    fused or not, flat or separate allocations: each compared bit for bit with the oracle."""
+    rng = np.random.default_rng(20230212)
+    picks = [1, 2, 3, 5, 7, 8, 31, 32, 33, 63, 64, 65, 100, 255, 256, 257, 1000, 1023, 1024, 1025,
+             4095, 4096, 4097, 8191, 8192, 8193, 12289, 20000, 40001]
+    for case in range(40):
+        L = int(rng.integers(1, 14))
+        sizes = [int(rng.choice(picks)) for _ in range(L)]
+        if rng.random() < 0.3:
+            sizes[int(rng.integers(0, L))] = int(rng.integers(50000, 300000))
+        P = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8, 9, 12, 16, 17, 24, 33]))
+        dtype = str(rng.choice(["f32", "bf16"]))
+        g = 4 if dtype == "f32" else 2
+        thr = int(rng.choice([0, 64 * g, 5000 * g, 30000 * g, 200000 * g, W.NO_LIMIT]))
+        width = int(rng.choice([0, 0, 1, 2, 7, 64, 256]))
+        fused = bool(rng.random() < 0.5)
+        per_bucket = bool(rng.random() < 0.5)
+        layout = str(rng.choice(["flat", "separate"]))
+        say("case: random %d sizes=%s P=%d %s thr=%d width=%d fused=%d per_bucket=%d %s" % (
+            case, sizes, P, dtype, thr, width, fused, per_bucket, layout))
+        pr = Pair(small_workload(sizes, P, thr, dtype, index=1000 + case), layout=layout)
+        pr.run(2, per_bucket=per_bucket, fused=fused, width=width)
+        pr.close()
