@@ -38,6 +38,7 @@ def _load():
     if _lib is None:
         _lib = C.CDLL(build())
         _lib.oracle_plan.restype = C.c_int32
+        _lib.oracle_plan_fixed_layers.restype = C.c_int32
         for name in ("oracle_reduce_scatter", "oracle_shard_update", "oracle_all_gather",
                      "oracle_scatter_params"):
             getattr(_lib, name).restype = None
@@ -95,6 +96,32 @@ def plan(sizes: Sequence[int], P: int, threshold_bytes: int, grad_elem_bytes: in
     if B < 0:
         raise ValueError("oracle_plan: invalid arguments")
     return OraclePlan(n, P, threshold_bytes, grad_elem_bytes, B, lb[:L], lo[:L],
+                      bf[:B].copy(), bn[:B].copy(), bl[:B].copy(), bs[:B].copy(), bb[:B].copy())
+
+
+def plan_fixed_layers(sizes: Sequence[int], P: int, layers_per_group: int,
+                      grad_elem_bytes: int = 4) -> OraclePlan:
+    """The fixed-number-of-layers grouping of the tensor-fusion study (Sec. VI-G).  The
+    returned plan has threshold_bytes = -1 (no buffer size is involved)."""
+    lib = _load()
+    n = np.ascontiguousarray(sizes, dtype=np.int64)
+    L = int(n.shape[0])
+    cap = max(L, 1)
+    lb = np.zeros(cap, np.int32)
+    lo = np.zeros(cap, np.int64)
+    bf = np.zeros(cap, np.int32)
+    bn = np.zeros(cap, np.int32)
+    bl = np.zeros(cap, np.int64)
+    bs = np.zeros(cap, np.int64)
+    bb = np.zeros(cap, np.int64)
+    B = lib.oracle_plan_fixed_layers(_p(n, C.c_int64), C.c_int32(L), C.c_int32(P),
+                                     C.c_int32(layers_per_group), C.c_int32(grad_elem_bytes),
+                                     _p(lb, C.c_int32), _p(lo, C.c_int64), _p(bf, C.c_int32),
+                                     _p(bn, C.c_int32), _p(bl, C.c_int64), _p(bs, C.c_int64),
+                                     _p(bb, C.c_int64))
+    if B < 0:
+        raise ValueError("oracle_plan_fixed_layers: invalid arguments")
+    return OraclePlan(n, P, -1, grad_elem_bytes, B, lb[:L], lo[:L],
                       bf[:B].copy(), bn[:B].copy(), bl[:B].copy(), bs[:B].copy(), bb[:B].copy())
 
 

@@ -11,6 +11,8 @@
  *                      while their total gradient count does not exceed the buffer
  *                      size x [Sec. IV-B; issue order Sec. III-B]; each group of d
  *                      elements is cut into P chunks, one per worker [Sec. III-A].
+ *   plan_fixed_layers -- the other grouping of the tensor-fusion study: a fixed number
+ *                      of consecutive layers per group [Sec. VI-G]; chunking as above.
  *   reduce_scatter  -- chunk s of every group is reduced onto worker s through P-1 ring
  *                      rounds [Sec. III-A, Eq. 3]; the 1/P of S-SGD is applied to the
  *                      finished sum [Eq. 2].
@@ -40,6 +42,22 @@
 #include <string.h>
 
 #define ORACLE_SHARD_ALIGN 32
+
+/* ------------------------------------------------------------- chunking [Sec. III-A] */
+/* Every group of d elements is cut into P chunks of d/P elements, one per worker; the
+ * chunk length is rounded up so that P chunks cover d and stay 32-element aligned. */
+static void cut_into_chunks(int32_t B, int32_t P, const int64_t *bucket_len,
+                            int64_t *bucket_shard_len, int64_t *bucket_shard_base)
+{
+    int64_t base = 0;
+    for (int32_t b = 0; b < B; ++b) {
+        int64_t per = (bucket_len[b] + P - 1) / P;
+        int64_t S = (per + ORACLE_SHARD_ALIGN - 1) / ORACLE_SHARD_ALIGN * ORACLE_SHARD_ALIGN;
+        bucket_shard_len[b] = S;
+        bucket_shard_base[b] = base;
+        base += S;
+    }
+}
 
 /* ------------------------------------------------------------------ plan [Sec. IV-B] */
 /* Outputs: layer_bucket[L], layer_offset[L]; per bucket (arrays of capacity L):
@@ -79,14 +97,47 @@ int32_t oracle_plan(const int64_t *n, int32_t L, int32_t P, int64_t x_bytes, int
     bucket_len[B] = tot;
     ++B;
 
-    int64_t base = 0;
-    for (int32_t b = 0; b < B; ++b) {       /* P chunks of d/P elements [Sec. III-A] */
-        int64_t per = (bucket_len[b] + P - 1) / P;
-        int64_t S = (per + ORACLE_SHARD_ALIGN - 1) / ORACLE_SHARD_ALIGN * ORACLE_SHARD_ALIGN;
-        bucket_shard_len[b] = S;
-        bucket_shard_base[b] = base;
-        base += S;
+    cut_into_chunks(B, P, bucket_len, bucket_shard_len, bucket_shard_base);
+    return B;
+}
+
+/* ------------------------------------------- plan, fixed number of layers [Sec. VI-G] */
+/* The naive grouping the tensor-fusion study compares against: every group is k
+ * consecutive layers, taken in gradient-ready order (last layer first), whatever their
+ * sizes; the layers left over at the front of the model form the last, shorter group.
+ * Outputs and return value as oracle_plan. */
+int32_t oracle_plan_fixed_layers(const int64_t *n, int32_t L, int32_t P, int32_t k, int32_t g,
+                                 int32_t *layer_bucket, int64_t *layer_offset,
+                                 int32_t *bucket_first_layer, int32_t *bucket_n_layers,
+                                 int64_t *bucket_len, int64_t *bucket_shard_len, int64_t *bucket_shard_base)
+{
+    if (L < 1 || P < 1 || k < 1 || (g != 2 && g != 4)) return -1;
+    for (int32_t l = 0; l < L; ++l)
+        if (n[l] < 1) return -1;
+
+    int32_t B = 0;
+    int64_t pos = 0;                        /* elements packed into the open group */
+    int32_t held = 0;                       /* layers in the open group            */
+    for (int32_t l = L - 1; l >= 0; --l) {  /* same arrival order as the threshold rule */
+        if (held == k) {                     /* the open group is full */
+            bucket_first_layer[B] = l + 1;
+            bucket_n_layers[B] = held;
+            bucket_len[B] = pos;
+            ++B;
+            pos = 0;
+            held = 0;
+        }
+        layer_bucket[l] = B;
+        layer_offset[l] = pos;
+        pos += n[l];
+        ++held;
     }
+    bucket_first_layer[B] = 0;
+    bucket_n_layers[B] = held;
+    bucket_len[B] = pos;
+    ++B;
+
+    cut_into_chunks(B, P, bucket_len, bucket_shard_len, bucket_shard_base);
     return B;
 }
 

@@ -46,16 +46,21 @@ def _check_replicas_and_pads(em, op, w):
         assert bool((flat.view(torch.int32) == 0).all())
 
 
-def test_bert_large_full_size_sampled_buckets():
+@pytest.mark.parametrize("name,n_buckets,sample", [
+    ("bert_large", 11, [0, 5, 10]),   # P = 8, bf16 gradients, 64 MB; bucket 10 = word embedding alone
+    ("bert_base", 7, [0, 3, 6]),      # P = 16, fp32 gradients, 64 MB; bucket 6 = the oversized embedding
+])
+def test_full_size_sampled_buckets(name, n_buckets, sample):
     from paper_2302_12445_amd.emulation import EmulatedWorkers
-    print("case: bert_large full size, buckets 0 / 5 / 10 recomputed by the oracle", flush=True)
-    w = W.get_workload("bert_large")
+    print("case: %s full size, buckets %s recomputed by the oracle" % (name, sample), flush=True)
+    w = W.get_workload(name)
     em = EmulatedWorkers(w.sizes, w.P, w.grad_dtype, w.threshold_bytes, DEV)
     op = oracle.plan(w.sizes, w.P, w.threshold_bytes, w.grad_elem_bytes)
-    assert op.n_buckets == 11
+    assert op.n_buckets == n_buckets
+    if name == "bert_base":   # the embedding tensor alone exceeds the buffer size and is never split
+        assert int(op.bucket_n_layers[6]) == 1 and int(op.bucket_len[6]) * 4 > w.threshold_bytes
     _fill(em, w)
     row = op.total_shard_len
-    sample = [0, 5, 10]
     grads = [[None] * w.n_layers for _ in range(w.P)]
     params = [[None] * w.n_layers for _ in range(w.P)]
     for b in sample:
@@ -140,5 +145,53 @@ def test_scale_stress_sampled_shards(name, buckets):
             for p in (0, 31, 63):
                 got = _host(em.params[p][l][a - off:c - off])
                 assert np.array_equal(got.view(np.uint32), sp[s, base + a - lo:base + c - lo].view(np.uint32)), (b, s, l, p)
+    _check_replicas_and_pads(em, op, w)
+    em.close()
+
+
+def test_scale_stress_one_bucket_every_shard_and_full_replicas():
+    """P = 64, 16 MB buckets: for one whole bucket the oracle is run over all 64 shards and the
+    GPU's three shard buffers are compared slot by slot; every parameter tensor of the bucket is
+    compared in full on replica 0 (and on the last replica)."""
+    from paper_2302_12445_amd.emulation import EmulatedWorkers
+    print("case: stress_16mb, bucket 12, all 64 shards, replica 0 in full", flush=True)
+    w = W.get_workload("stress_16mb")
+    em = EmulatedWorkers(w.sizes, w.P, w.grad_dtype, w.threshold_bytes, DEV)
+    op = oracle.plan(w.sizes, w.P, w.threshold_bytes, w.grad_elem_bytes)
+    assert op.n_buckets == 26
+    _fill(em, w)
+    b = 12
+    layers = _bucket_layers(op, b)
+    assert len(layers) > 1
+    grads = [[None] * w.n_layers for _ in range(w.P)]
+    params = [[None] * w.n_layers for _ in range(w.P)]
+    for l in layers:
+        for p in range(w.P):
+            grads[p][l] = _host(em.grads[p][l])
+        for p in (0, w.P - 1):
+            params[p][l] = _host(em.params[p][l]).copy()
+    row = op.total_shard_len
+    sg = np.zeros((w.P, row), np.float32)
+    sp, sm = np.zeros_like(sg), np.zeros_like(sg)
+    oracle.scatter_params(op, params, 0, sp, bucket=b)
+
+    em.shard_grad.fill_(float("nan"))
+    for p in (0, w.P - 1):
+        for l in layers:
+            em.params[p][l].fill_(float("nan"))
+    em.iteration(w.lr, w.momentum, per_bucket=True)
+    torch.cuda.synchronize()
+
+    oracle.reduce_scatter(op, b, grads, sg)
+    oracle.shard_update(op, b, sg, sp, sm, w.lr, w.momentum)
+    oracle.all_gather(op, b, sp, params, workers=range(0, 1))
+    oracle.all_gather(op, b, sp, params, workers=range(w.P - 1, w.P))
+    lo, S = int(op.bucket_shard_base[b]), int(op.bucket_shard_len[b])
+    for nm, dev, ref in (("grad", em.shard_grad, sg), ("param", em.shard_param, sp), ("mom", em.shard_mom, sm)):
+        got = dev[:, lo:lo + S].cpu().numpy()
+        assert np.array_equal(got.view(np.uint32), ref[:, lo:lo + S].view(np.uint32)), nm
+    for p in (0, w.P - 1):
+        for l in layers:
+            assert np.array_equal(_host(em.params[p][l]).view(np.uint32), params[p][l].view(np.uint32)), (p, l)
     _check_replicas_and_pads(em, op, w)
     em.close()

@@ -33,11 +33,14 @@ def _bits(a: np.ndarray) -> np.ndarray:
 class Pair:
     """The same problem on both sides: EmulatedWorkers on the GPU, numpy + oracle on the CPU."""
 
-    def __init__(self, w: W.Workload, layout="flat", plan=None):
+    def __init__(self, w: W.Workload, layout="flat", plan=None, oracle_plan=None):
+        """plan / oracle_plan: the two sides' own plans when the grouping is not the
+        workload's threshold rule (each side builds its plan with its own planner)."""
         from paper_2302_12445_amd.emulation import EmulatedWorkers
         self.w = w
         self.em = EmulatedWorkers(w.sizes, w.P, w.grad_dtype, w.threshold_bytes, DEV, layout, plan)
-        self.op = oracle.plan(w.sizes, w.P, w.threshold_bytes, w.grad_elem_bytes)
+        self.op = oracle_plan if oracle_plan is not None else oracle.plan(
+            w.sizes, w.P, w.threshold_bytes, w.grad_elem_bytes)
         row = self.op.total_shard_len
         assert row == self.em.plan.total_shard_len
         self.sg = np.zeros((w.P, row), np.float32)
@@ -204,35 +207,37 @@ def test_many_tiles_per_shard(dtype):
     pr.close()
 
 
-def test_fixed_layers_plan():
-    """The fixed-number-of-layers grouping drives the same kernels.  The oracle has no such
-    rule, so the result is compared with the single-bucket oracle run: grouping changes
-    which shard (and ring start) owns an element, so values may differ in the last bits
-    but must agree to the summation bound, and all replicas must be identical."""
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("layers_per_bucket", [4, 3])
+def test_fixed_layers_plan(dtype, layers_per_bucket):
+    """The fixed-number-of-layers grouping of the tensor-fusion study (Section VI-G) drives the
+    same kernels: the library's plan and the oracle's own fixed-layers plan, bit for bit over
+    the shards of every worker and the parameters of every replica, three iterations."""
     import paper_2302_12445_amd as dear
-    from paper_2302_12445_amd.emulation import EmulatedWorkers
-    say("case: fixed-layers plan")
-    w = small_workload(RAGGED, 4, W.NO_LIMIT, "f32", index=51)
-    plan = dear.dear_plan_fixed_layers(w.sizes, 4, 4, 4)
-    assert plan.n_buckets == 3
-    em = EmulatedWorkers(w.sizes, 4, "f32", 0, DEV, plan=plan)
-    ref = Pair(w)
-    ref.seed_shards()
-    ref.load_grads(0)
-    ref.oracle_iteration()
-    for p in range(4):
-        em.load_dense(em.params[p], W.make_flat_param(w).to(DEV))
-        em.load_dense(em.grads[p], W.make_flat_grad(w, p, 0).to(DEV))
-    em.scatter_params(0)
-    em.iteration(w.lr, w.momentum)
-    torch.cuda.synchronize()
-    for l in range(w.n_layers):
-        a = em.params[0][l].cpu().numpy()
-        assert np.allclose(a, ref.params[0][l], rtol=0, atol=1e-8)
-        for p in range(1, 4):
-            assert torch.equal(em.params[p][l], em.params[0][l])
-    em.close()
-    ref.close()
+    say("case: fixed-layers plan, %d layers per bucket, %s" % (layers_per_bucket, dtype))
+    g = 4 if dtype == "f32" else 2
+    w = small_workload(RAGGED, 4, W.NO_LIMIT, dtype, index=51)
+    plan = dear.dear_plan_fixed_layers(w.sizes, w.P, layers_per_bucket, g)
+    op = oracle.plan_fixed_layers(w.sizes, w.P, layers_per_bucket, g)
+    assert plan.n_buckets == op.n_buckets == -(-len(RAGGED) // layers_per_bucket)
+    pr = Pair(w, plan=plan, oracle_plan=op)
+    pr.run(3)
+    pr.run(1, fused=True)
+    pr.close()
+
+
+def test_fixed_layers_plan_resnet50_shape():
+    """Four layers per bucket (the paper's number) on the ResNet-50 tensor list: 41 buckets of
+    very uneven size, one launch per bucket."""
+    import paper_2302_12445_amd as dear
+    say("case: fixed-layers plan, resnet50 shape")
+    w = W.get_workload("resnet50")
+    plan = dear.dear_plan_fixed_layers(w.sizes, w.P, 4, 4)
+    op = oracle.plan_fixed_layers(w.sizes, w.P, 4, 4)
+    assert plan.n_buckets == op.n_buckets == 41
+    pr = Pair(w, plan=plan, oracle_plan=op)
+    pr.run(1)
+    pr.close()
 
 
 def test_signed_zero_nan_inf():

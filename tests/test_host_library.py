@@ -78,6 +78,24 @@ def test_plan_fixed_layers():
     assert dear.dear_plan_fixed_layers(sizes, 3, 1, 4).n_buckets == len(sizes)
 
 
+def test_plan_fixed_layers_matches_oracle():
+    """Integer parity of dear_plan_fixed_layers with the oracle's fixed-layers rule (Sec. VI-G)."""
+    rng = np.random.default_rng(777)
+    for _ in range(300):
+        L = int(rng.integers(1, 50))
+        sizes = [int(v) for v in rng.integers(1, 9000, size=L)]
+        P = int(rng.integers(1, 70))
+        g = int(rng.choice([2, 4]))
+        K = int(rng.integers(1, 60))
+        assert_plans_equal(dear.dear_plan_fixed_layers(sizes, P, K, g), oracle.plan_fixed_layers(sizes, P, K, g))
+    for name in ("resnet50", "densenet201", "bert_base", "bert_large"):
+        w = W.get_workload(name)
+        assert_plans_equal(dear.dear_plan_fixed_layers(w.sizes, w.P, 4, w.grad_elem_bytes),
+                           oracle.plan_fixed_layers(w.sizes, w.P, 4, w.grad_elem_bytes))
+    big = [2 ** 40, 2 ** 41 + 5, 7]
+    assert_plans_equal(dear.dear_plan_fixed_layers(big, 64, 2, 4), oracle.plan_fixed_layers(big, 64, 2, 4))
+
+
 def test_plan_argument_errors():
     for args in (([], 2, 10, 4), ([1, 0], 2, 10, 4), ([1], 0, 10, 4), ([1], 2, -1, 4), ([1], 2, 10, 3)):
         with pytest.raises(dear.DearError) as e:

@@ -27,6 +27,13 @@ MUTATIONS = [
      [pins.test_plan_worked_example_tiny]),
     ("shard length not rounded up from d/P", "(bucket_len[b] + P - 1) / P", "bucket_len[b] / P",
      [pins.test_plan_invariants_random]),
+    ("fixed-layers group takes one layer too many", "if (held == k) {", "if (held == k + 1) {",
+     [pins.test_fixed_layers_worked_example_tiny, pins.test_fixed_layers_invariants_random]),
+    ("fixed-layers groups counted from the first layer",
+     "for (int32_t l = L - 1; l >= 0; --l) {  /* same arrival order as the threshold rule */",
+     "for (int32_t l = 0; l < L; ++l) {", [pins.test_fixed_layers_worked_example_tiny]),
+    ("fixed-layers offsets not reset at a new group", "            pos = 0;\n            held = 0;",
+     "            held = 0;", [pins.test_fixed_layers_worked_example_tiny]),
     ("ring sum starts at the owner", "grad_at(grad, L, g, (s + 1) % P, l, i);", "grad_at(grad, L, g, (s + 0) % P, l, i);",
      [lambda: pins.test_ring_order_matches_message_passing(4), pins.test_ring_order_is_observable]),
     ("ring runs the other way", "(s + k) % P, l, i);", "(s + 2 * P - k + 2) % P, l, i);",
@@ -61,6 +68,7 @@ MUTATIONS = [
 def _load(path):
     lib = C.CDLL(path)
     lib.oracle_plan.restype = C.c_int32
+    lib.oracle_plan_fixed_layers.restype = C.c_int32
     for name in ("oracle_reduce_scatter", "oracle_shard_update", "oracle_all_gather", "oracle_scatter_params"):
         getattr(lib, name).restype = None
     return lib

@@ -134,6 +134,86 @@ def test_plan_rejects_bad_arguments():
             oracle.plan(*args)
 
 
+# ----------------------------------------------------------------- plan: fixed number of layers
+def test_fixed_layers_worked_example_tiny():
+    """Section VI-G's naive grouping (a fixed number of nearby layers), hand-worked for the
+    Tiny layer list with four layers per group (the paper's number) and with three."""
+    w = W.get_workload("tiny")
+    rows = list(_rows(os.path.join(GOLDEN, "tiny_fixed_layers_plan.txt")))
+    for K in (4, 3):
+        pl = oracle.plan_fixed_layers(w.sizes, w.P, K, 4)
+        buckets = [r[1:] for r in rows if r[0] == str(K)]
+        layers = [r[2:] for r in rows if r[0] == "L" and r[1] == str(K)]
+        assert pl.n_buckets == len(buckets) == (2 if K == 4 else 3)
+        assert len(layers) == 8
+        for b, first, cnt, d, S, base in buckets:
+            b = int(b)
+            assert pl.bucket_first_layer[b] == int(first)
+            assert pl.bucket_n_layers[b] == int(cnt)
+            assert pl.bucket_len[b] == int(d)
+            assert pl.bucket_shard_len[b] == int(S)
+            assert pl.bucket_shard_base[b] == int(base)
+        for l, b, off in layers:
+            assert pl.layer_bucket[int(l)] == int(b)
+            assert pl.layer_offset[int(l)] == int(off)
+
+
+def check_fixed_layers_invariants(sizes, P, K, pl):
+    """What singles out the fixed-layers plan: groups are runs of exactly K consecutive
+    layers taken last-to-first, only the final group (the model's first layers) may be
+    shorter, layers are packed densely in arrival order, chunking as for any group."""
+    L = len(sizes)
+    B = pl.n_buckets
+    assert B == -(-L // K)
+    nxt = L
+    for b in range(B):
+        first, cnt, d = int(pl.bucket_first_layer[b]), int(pl.bucket_n_layers[b]), int(pl.bucket_len[b])
+        assert first + cnt == nxt
+        assert cnt == (K if b < B - 1 else L - K * (B - 1))
+        nxt = first
+        assert d == sum(sizes[first:first + cnt])
+        off = 0
+        for l in range(first + cnt - 1, first - 1, -1):
+            assert pl.layer_bucket[l] == b and pl.layer_offset[l] == off
+            off += sizes[l]
+        S = int(pl.bucket_shard_len[b])
+        assert S % 32 == 0 and P * S >= d and (S == 32 or (S - 32) * P < d)
+        assert pl.bucket_shard_base[b] == sum(int(s) for s in pl.bucket_shard_len[:b])
+    assert nxt == 0
+
+
+def test_fixed_layers_invariants_random():
+    rng = np.random.default_rng(4321)
+    for _ in range(300):
+        L = int(rng.integers(1, 40))
+        sizes = [int(v) for v in rng.integers(1, 5000, size=L)]
+        P = int(rng.integers(1, 12))
+        K = int(rng.integers(1, 45))
+        check_fixed_layers_invariants(sizes, P, K, oracle.plan_fixed_layers(sizes, P, K, int(rng.choice([2, 4]))))
+    for name in ("resnet50", "bert_base"):   # the models of the paper's study, four layers per group
+        w = W.get_workload(name)
+        check_fixed_layers_invariants(w.sizes, w.P, 4, oracle.plan_fixed_layers(w.sizes, w.P, 4, 4))
+
+
+def test_fixed_layers_special_cases_reduce_to_the_threshold_rule():
+    """One layer per group is the no-fusion plan (x = 0); at least L layers per group is the
+    single-group plan (no limit): there the two grouping rules must agree table by table."""
+    rng = np.random.default_rng(99)
+    for _ in range(50):
+        L = int(rng.integers(1, 30))
+        sizes = [int(v) for v in rng.integers(1, 3000, size=L)]
+        P = int(rng.integers(1, 9))
+        for K, x in ((1, 0), (L, W.NO_LIMIT), (L + 3, W.NO_LIMIT)):
+            a, b = oracle.plan_fixed_layers(sizes, P, K, 4), oracle.plan(sizes, P, x, 4)
+            assert a.n_buckets == b.n_buckets
+            for f in ("layer_bucket", "layer_offset", "bucket_first_layer", "bucket_n_layers", "bucket_len",
+                      "bucket_shard_len", "bucket_shard_base"):
+                assert np.array_equal(getattr(a, f), getattr(b, f)), f
+    for args in (([], 2, 1, 4), ([1, 0], 2, 1, 4), ([1], 0, 1, 4), ([1], 2, 0, 4), ([1], 2, 1, 3)):
+        with pytest.raises(ValueError):
+            oracle.plan_fixed_layers(*args)
+
+
 def test_slot_map_is_a_bijection():
     """Every (layer, element) lands on exactly one non-pad slot; pads stay untouched."""
     sizes = [13, 1, 70, 33, 5, 64, 2]
