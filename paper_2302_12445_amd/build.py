@@ -10,6 +10,10 @@ CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libdear.so")
 SOURCES = [os.path.join(CSRC, "plan.cpp"), os.path.join(CSRC, "dear_hip.hip")]
 HEADERS = [os.path.join(CSRC, "dear_internal.h"), os.path.join(ROOT, "include", "dear.h")]
+# measurement aid, a library of its own: bare HBM traffic patterns (include/dear_probe.h)
+PROBE_LIB = os.path.join(PKG, "libdear_probe.so")
+PROBE_SOURCES = [os.path.join(CSRC, "hbm_probe.hip")]
+PROBE_HEADERS = [os.path.join(ROOT, "include", "dear_probe.h")]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
@@ -22,24 +26,39 @@ HIPCC_FLAGS = [
 ]
 
 
-def is_stale() -> bool:
-    if not os.path.exists(LIB):
+def _stale(lib, deps) -> bool:
+    if not os.path.exists(lib):
         return True
-    t = os.path.getmtime(LIB)
-    return any(os.path.getmtime(f) > t for f in SOURCES + HEADERS)
+    t = os.path.getmtime(lib)
+    return any(os.path.getmtime(f) > t for f in deps)
+
+
+def is_stale() -> bool:
+    return _stale(LIB, SOURCES + HEADERS)
+
+
+def _compile(lib, sources, extra_flags=()) -> str:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    tmp = lib + ".tmp.%d" % os.getpid()
+    subprocess.run([hipcc, *HIPCC_FLAGS, *extra_flags, "-o", tmp, *sources], check=True)
+    os.replace(tmp, lib)
+    return lib
 
 
 def build(force: bool = True, extra_flags=()) -> str:
-    """Compile the library.  With force=False an up-to-date library is kept."""
+    """Compile libdear.so.  With force=False an up-to-date library is kept."""
     if not force and not is_stale():
         return LIB
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-o", tmp, *SOURCES]
-    subprocess.run(cmd, check=True)
-    os.replace(tmp, LIB)
-    return LIB
+    return _compile(LIB, SOURCES, extra_flags)
+
+
+def build_probe(force: bool = True) -> str:
+    """Compile libdear_probe.so (the HBM stream-pattern probe)."""
+    if not force and not _stale(PROBE_LIB, PROBE_SOURCES + PROBE_HEADERS):
+        return PROBE_LIB
+    return _compile(PROBE_LIB, PROBE_SOURCES)
 
 
 if __name__ == "__main__":
     print(build())
+    print(build_probe())

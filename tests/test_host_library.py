@@ -29,6 +29,24 @@ def test_library_exports_every_declared_symbol():
     assert dear.strerror(0) == "ok" and "align" in dear.strerror(-5)
 
 
+def test_probe_library_exports_every_declared_symbol():
+    from paper_2302_12445_amd import hbm_probe
+    header = open(os.path.join(ROOT, "include", "dear_probe.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(dear_[a-z_]+)\s*\(", header))
+    assert declared == set(hbm_probe.EXPORTS)
+    lib = hbm_probe.load_library()
+    for name in declared:
+        assert hasattr(lib, name), name
+    out = C.c_double()
+    # argument errors are rejected before any HIP call
+    assert lib.dear_probe_streams(0, 0, 1 << 20, 0, 4, 1, C.byref(out), None) == -1
+    assert lib.dear_probe_streams(0, 8, 1000, 0, 4, 1, C.byref(out), None) == -1
+    assert lib.dear_probe_streams(9, 8, 1 << 20, 0, 4, 1, C.byref(out), None) == -1
+    assert lib.dear_probe_streams(1, 8, 1 << 20, 0, 2, 1, C.byref(out), None) == -1
+    assert lib.dear_probe_streams(0, 8, 1 << 20, 0, 4, 1, None, None) == -1
+
+
 def assert_plans_equal(lp, op):
     assert lp.n_buckets == op.n_buckets and lp.P == op.P and lp.n_layers == op.L
     assert lp.total_shard_len == op.total_shard_len and lp.total_elems == op.total_elems
