@@ -41,12 +41,16 @@ enum {
  *   chunk_bytes       chunk of the CHUNKED pattern (multiple of 4096), ignored otherwise
  *   elem_bytes_in     2 or 4: bytes read per output element in READ_K_WRITE_1 (2 = bf16
  *                     inputs widened to a 4-byte output); 4 for the other patterns
+ *   skew_bytes        stream j starts j * skew_bytes into its own allocation (multiple of 256,
+ *                     at most 64 MiB; 0 = every stream starts at its allocation's base): shifts
+ *                     which HBM channel and bank the k streams touch at the same moment
  *   reps              timed launches (>= 1), after two untimed ones
  *   gbytes_per_s      host, receives (bytes read + bytes written per launch) / time, in 1e9 B/s
  *   avg_ms            host, receives the average launch time in milliseconds (may be NULL)
  * Returns 0, -1 for a bad argument, -2 if an allocation failed, -3 for a HIP error. */
 int dear_probe_streams(int32_t pattern, int32_t k, int64_t bytes_per_stream, int64_t chunk_bytes,
-                       int32_t elem_bytes_in, int32_t reps, double *gbytes_per_s, double *avg_ms);
+                       int32_t elem_bytes_in, int64_t skew_bytes, int32_t reps, double *gbytes_per_s,
+                       double *avg_ms);
 
 #ifdef __cplusplus
 }

@@ -108,24 +108,27 @@ struct buffers {
     {
         for (void *p : all) (void)hipFree(p);
     }
-    void *get(size_t bytes)
+    // `lead` unused bytes in front: stream j of a pattern starts j*skew into its allocation
+    void *get(size_t bytes, size_t lead = 0)
     {
         void *p = nullptr;
-        if (hipMalloc(&p, bytes) != hipSuccess) {
+        if (hipMalloc(&p, bytes + lead) != hipSuccess) {
             (void)hipGetLastError();
             return nullptr;
         }
         all.push_back(p);
-        if (hipMemset(p, 0, bytes) != hipSuccess) return nullptr;
-        return p;
+        if (hipMemset(p, 0, bytes + lead) != hipSuccess) return nullptr;
+        return static_cast<unsigned char *>(p) + lead;
     }
 };
 
 }  // namespace
 
 extern "C" int dear_probe_streams(int32_t pattern, int32_t k, int64_t bytes_per_stream, int64_t chunk_bytes,
-                                  int32_t elem_bytes_in, int32_t reps, double *gbytes_per_s, double *avg_ms)
+                                  int32_t elem_bytes_in, int64_t skew_bytes, int32_t reps, double *gbytes_per_s,
+                                  double *avg_ms)
 {
+    if (skew_bytes < 0 || skew_bytes % 256 || skew_bytes > (1 << 26)) return -1;
     if (!gbytes_per_s || reps < 1 || bytes_per_stream < 4096 || bytes_per_stream % 4096) return -1;
     if (pattern < DEAR_PROBE_READ_K_WRITE_1 || pattern > DEAR_PROBE_READ_3_WRITE_2) return -1;
     if (pattern != DEAR_PROBE_READ_3_WRITE_2 && (k < 1 || k > MAX_K)) return -1;
@@ -145,7 +148,7 @@ extern "C" int dear_probe_streams(int32_t pattern, int32_t k, int64_t bytes_per_
         bytes_moved = 5.0 * bytes_per_stream;
     } else {
         for (int j = 0; j < k; ++j)
-            if (!(tab.ptr[j] = mem.get(bytes_per_stream))) return -2;
+            if (!(tab.ptr[j] = mem.get(bytes_per_stream, static_cast<size_t>(j) * skew_bytes))) return -2;
         const int64_t single_bytes = (pattern == DEAR_PROBE_READ_K_WRITE_1 && elem_bytes_in == 2) ? 2 * bytes_per_stream
                                                                                                     : bytes_per_stream;
         if (!(single = mem.get(single_bytes))) return -2;

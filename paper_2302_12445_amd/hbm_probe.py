@@ -30,18 +30,18 @@ def load_library() -> C.CDLL:
             raise ImportError("libdear_probe.so is not built: run `python -m paper_2302_12445_amd.build`")
         import torch  # noqa: F401  (one HIP runtime per process: torch's copy is loaded first)
         lib = C.CDLL(LIB_PATH)
-        lib.dear_probe_streams.argtypes = [C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_int32, C.c_int32,
-                                           C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        lib.dear_probe_streams.argtypes = [C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_int32, C.c_int64,
+                                           C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         lib.dear_probe_streams.restype = C.c_int
         _lib = lib
     return _lib
 
 
 def dear_probe_streams(pattern: int, k: int, bytes_per_stream: int, chunk_bytes: int = 0,
-                       elem_bytes_in: int = 4, reps: int = 10) -> Dict[str, float]:
+                       elem_bytes_in: int = 4, reps: int = 10, skew_bytes: int = 0) -> Dict[str, float]:
     gbps, ms = C.c_double(), C.c_double()
-    rc = load_library().dear_probe_streams(pattern, k, bytes_per_stream, chunk_bytes, elem_bytes_in, reps,
-                                           C.byref(gbps), C.byref(ms))
+    rc = load_library().dear_probe_streams(pattern, k, bytes_per_stream, chunk_bytes, elem_bytes_in, skew_bytes,
+                                           reps, C.byref(gbps), C.byref(ms))
     if rc != 0:
         raise RuntimeError("dear_probe_streams: status %d" % rc)
     return {"GBps": gbps.value, "ms": ms.value}
@@ -51,10 +51,10 @@ def sweep(bytes_per_stream: int = 1 << 30, reps: int = 10) -> List[dict]:
     """The patterns of the three kernels at the worker counts of the benchmark workloads."""
     rows = []
 
-    def run(pattern, k, elem=4, chunk=0, per_stream=bytes_per_stream):
-        r = dear_probe_streams(pattern, k, per_stream, chunk, elem, reps)
+    def run(pattern, k, elem=4, chunk=0, per_stream=bytes_per_stream, skew=0):
+        r = dear_probe_streams(pattern, k, per_stream, chunk, elem, reps, skew)
         rows.append({"pattern": PATTERN_NAMES[pattern], "k": k, "elem_bytes_in": elem,
-                     "chunk_MiB": chunk >> 20, "bytes_per_stream_MiB": per_stream >> 20,
+                     "chunk_MiB": chunk >> 20, "skew_bytes": skew, "bytes_per_stream_MiB": per_stream >> 20,
                      "GBps": round(r["GBps"], 1), "ms": round(r["ms"], 4), "frac_of_8TBps": round(r["GBps"] / 8000, 4)})
 
     for k in (1, 2, 4, 8, 16):
@@ -67,6 +67,9 @@ def sweep(bytes_per_stream: int = 1 << 30, reps: int = 10) -> List[dict]:
         run(READ_1_WRITE_K_CHUNKED, 8, chunk=chunk)
     run(READ_1_WRITE_K_CHUNKED, 16, chunk=8 << 20)
     run(READ_3_WRITE_2, 3)
+    for skew in (256, 4096, 65536 + 4096, (1 << 20) + 8192):   # does shifting the streams against each other help?
+        run(READ_K_WRITE_1, 8, skew=skew)
+        run(READ_1_WRITE_K, 8, skew=skew)
     return rows
 
 

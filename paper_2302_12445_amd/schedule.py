@@ -32,14 +32,24 @@ class DearSchedule:
     def __init__(self, em: EmulatedWorkers, lr: float, momentum: float, gemm_dim: int = 4096,
                  ff_gemms: int = 1, bp_gemms: int = 2,
                  on_backward: Optional[Callable[[int, int], None]] = None,
-                 overlap_workgroups: int = 256, overlap_workgroups_ag: Optional[int] = 192):
+                 overlap_workgroups: int = 256, overlap_workgroups_ag: Optional[int] = 192,
+                 fused_update: bool = False, gemm_dtype: torch.dtype = torch.float32,
+                 full_width_when_alone: bool = False,
+                 compute_stream: Optional[torch.cuda.Stream] = None,
+                 comm_stream: Optional[torch.cuda.Stream] = None):
         """on_backward(iteration, bucket) runs on the compute stream behind the bucket's
         backward GEMMs; tests use it to write that bucket's fresh gradients.
         overlap_workgroups bounds the grid of the aggregation kernels in the overlapping
         modes (dear, wfbp); 0 leaves them unbounded.  overlap_workgroups_ag, if given, is
         the bound for the all-gather (the forward pass it hides under is half as long as
-        the backward pass, so it may need a wider grid)."""
+        the backward pass, so it may need a wider grid).
+        fused_update: reduce-scatter and update of a bucket in one kernel (fewer bytes).
+        full_width_when_alone: in mode dear, the kernels that can have no compute beside
+        them (the last bucket's reduce-scatter/update after the backward pass has ended,
+        and the first all-gather the forward pass waits for) run with an unbounded grid."""
         self.em, self.lr, self.momentum = em, lr, momentum
+        self.fused_update = fused_update
+        self.full_width_when_alone = full_width_when_alone
         self.overlap_workgroups = overlap_workgroups
         self.overlap_workgroups_ag = overlap_workgroups if overlap_workgroups_ag is None else overlap_workgroups_ag
         if overlap_workgroups == 0:
@@ -48,11 +58,11 @@ class DearSchedule:
         self.ff_gemms, self.bp_gemms = ff_gemms, bp_gemms
         self.on_backward = on_backward
         dev = em.device
-        self.compute = torch.cuda.Stream(device=dev)
-        self.comm = torch.cuda.Stream(device=dev)
-        self.a = torch.randn(gemm_dim, gemm_dim, device=dev, dtype=torch.float32)
-        self.b = torch.randn(gemm_dim, gemm_dim, device=dev, dtype=torch.float32)
-        self.c = torch.empty(gemm_dim, gemm_dim, device=dev, dtype=torch.float32)
+        self.compute = compute_stream if compute_stream is not None else torch.cuda.Stream(device=dev)
+        self.comm = comm_stream if comm_stream is not None else torch.cuda.Stream(device=dev)
+        self.a = torch.randn(gemm_dim, gemm_dim, device=dev, dtype=torch.float32).to(gemm_dtype)
+        self.b = torch.randn(gemm_dim, gemm_dim, device=dev, dtype=torch.float32).to(gemm_dtype)
+        self.c = torch.empty(gemm_dim, gemm_dim, device=dev, dtype=gemm_dtype)
         self.grad_ready = [torch.cuda.Event() for _ in range(self.nb)]
         self.rs_done = [torch.cuda.Event() for _ in range(self.nb)]
         self.ag_done = [torch.cuda.Event() for _ in range(self.nb)]
@@ -87,8 +97,11 @@ class DearSchedule:
                     self.grad_ready[b].record(self.compute)
 
     def _reduce_scatter_and_update(self, b: int, stream) -> None:
-        self.em.reduce_scatter(b, stream)
-        self.em.shard_update(b, self.lr, self.momentum, stream)
+        if self.fused_update:
+            self.em.reduce_scatter_update(b, self.lr, self.momentum, stream)
+        else:
+            self.em.reduce_scatter(b, stream)
+            self.em.shard_update(b, self.lr, self.momentum, stream)
 
     # -------------------------------------------------------------- one iteration
     def iteration(self, mode: str = "dear") -> None:
@@ -137,14 +150,17 @@ class DearSchedule:
             self._forward(True)
             # BackPipe: OP1 of a bucket as soon as its gradients are ready
             self._backward(True)
+            alone = self.full_width_when_alone
             for b in range(nb):
                 self.comm.wait_event(self.grad_ready[b])
+                if alone and b == nb - 1:   # the backward pass has ended: nothing runs beside it
+                    em.set_max_workgroups(0)
                 self._reduce_scatter_and_update(b, self.comm)
                 self.rs_done[b].record(self.comm)
             # all OP1 precede every OP2: in order on the one communication stream.
             # OP2 in forward order, to be hidden under the next forward pass
-            em.set_max_workgroups(w_ag)
             for b in reversed(range(nb)):
+                em.set_max_workgroups(0 if (alone and b == nb - 1) else w_ag)   # the forward pass waits for the first
                 em.all_gather(b, self.comm)
                 self.ag_done[b].record(self.comm)
             self._have_ag = True

@@ -40,11 +40,12 @@ def test_probe_library_exports_every_declared_symbol():
         assert hasattr(lib, name), name
     out = C.c_double()
     # argument errors are rejected before any HIP call
-    assert lib.dear_probe_streams(0, 0, 1 << 20, 0, 4, 1, C.byref(out), None) == -1
-    assert lib.dear_probe_streams(0, 8, 1000, 0, 4, 1, C.byref(out), None) == -1
-    assert lib.dear_probe_streams(9, 8, 1 << 20, 0, 4, 1, C.byref(out), None) == -1
-    assert lib.dear_probe_streams(1, 8, 1 << 20, 0, 2, 1, C.byref(out), None) == -1
-    assert lib.dear_probe_streams(0, 8, 1 << 20, 0, 4, 1, None, None) == -1
+    assert lib.dear_probe_streams(0, 0, 1 << 20, 0, 4, 0, 1, C.byref(out), None) == -1
+    assert lib.dear_probe_streams(0, 8, 1000, 0, 4, 0, 1, C.byref(out), None) == -1
+    assert lib.dear_probe_streams(9, 8, 1 << 20, 0, 4, 0, 1, C.byref(out), None) == -1
+    assert lib.dear_probe_streams(1, 8, 1 << 20, 0, 2, 0, 1, C.byref(out), None) == -1
+    assert lib.dear_probe_streams(0, 8, 1 << 20, 0, 4, 100, 1, C.byref(out), None) == -1
+    assert lib.dear_probe_streams(0, 8, 1 << 20, 0, 4, 0, 1, None, None) == -1
 
 
 def assert_plans_equal(lp, op):
