@@ -38,7 +38,8 @@ enum {
     DEAR_ENOMEM = -2, /* host or device allocation of a library table failed       */
     DEAR_EHIP = -3,   /* a HIP call or a kernel launch reported an error           */
     DEAR_ERANGE = -4, /* bucket / worker index outside the plan                    */
-    DEAR_EALIGN = -5  /* a device pointer is not aligned as documented             */
+    DEAR_EALIGN = -5, /* a device pointer is not aligned as documented             */
+    DEAR_ETOOBIG = -6 /* input exceeds the static device scratch (see below)       */
 };
 
 enum { DEAR_F32 = 0, DEAR_BF16 = 1 }; /* gradient element type */
@@ -199,6 +200,42 @@ int dear_ctx_set_max_workgroups(dear_ctx_t *ctx, int32_t max_workgroups);
  * Errors: DEAR_EINVAL, DEAR_ERANGE, DEAR_EALIGN, DEAR_EHIP.
  */
 int dear_reduce_scatter(dear_ctx_t *ctx, int32_t bucket, float *shard_grad, void *hip_stream);
+
+/* ---------------------------------------------------------------------------------
+ * dear_reduce_scatter_static -- dear_reduce_scatter for callers that cannot allocate
+ * device memory: tight serving or training loops and harnesses that forbid hipMalloc
+ * once running, where creating a context (which allocates its tile and pointer tables)
+ * is not possible.  It needs no context and calls neither hipMalloc nor hipFree nor any
+ * other allocating routine, on the device or the host: the two tables its kernel reads
+ * are built in a fixed host staging area and uploaded into a fixed device array that
+ * the library holds on every GPU it runs on until the process ends
+ * (DEAR_STATIC_MAX_POINTERS * 8 + DEAR_STATIC_MAX_TILES * 32 bytes = 4 MiB).
+ *
+ *   plan        host, as for dear_ctx_create
+ *   grad_dtype  DEAR_F32 or DEAR_BF16, must agree with the plan
+ *   grad_ptrs   host array of P*n_layers DEVICE pointers, index [p*n_layers + l], each
+ *               16-byte aligned (read during the call; may be reused afterwards)
+ *   bucket      0 .. n_buckets-1, or -1 for every bucket in one launch
+ *   shard_grad  device, written; layout and values exactly as dear_reduce_scatter
+ *
+ * Limits: P*n_layers <= DEAR_STATIC_MAX_POINTERS and the processed buckets must cut into
+ * at most DEAR_STATIC_MAX_TILES tiles (one tile per DEAR_TILE_ELEMS elements of a layer
+ * within a shard, plus ragged ends: about 400 M elements); beyond that DEAR_ETOOBIG is
+ * returned and nothing is launched.
+ * The call uploads the tables on hip_stream, waits for that stream (so work queued on it
+ * earlier has finished when the call returns), then enqueues the kernel and returns
+ * without waiting for it.  Uses the current HIP device.  All calls on one GPU share that
+ * GPU's array, which keeps the last call's tables: nothing in it needs clearing (every
+ * entry the kernel reads is rewritten by the call), but calls that overlap on one GPU --
+ * different host threads, or a second call on another stream while the first call's
+ * kernel still runs -- race and must be serialised by the caller.
+ * Errors: DEAR_EINVAL, DEAR_ERANGE, DEAR_EALIGN, DEAR_ETOOBIG, DEAR_EHIP.
+ */
+#define DEAR_STATIC_MAX_POINTERS 131072
+#define DEAR_STATIC_MAX_TILES 98304
+int dear_reduce_scatter_static(const dear_plan_t *plan, int32_t grad_dtype,
+                               const void *const *grad_ptrs, int32_t bucket, float *shard_grad,
+                               void *hip_stream);
 
 /* ---------------------------------------------------------------------------------
  * dear_shard_update -- SGD with momentum on the owned shards of a bucket.

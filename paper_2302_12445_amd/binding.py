@@ -14,7 +14,8 @@ from typing import Optional, Sequence
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdear.so")
 
-DEAR_OK, DEAR_EINVAL, DEAR_ENOMEM, DEAR_EHIP, DEAR_ERANGE, DEAR_EALIGN = 0, -1, -2, -3, -4, -5
+DEAR_OK, DEAR_EINVAL, DEAR_ENOMEM, DEAR_EHIP, DEAR_ERANGE, DEAR_EALIGN, DEAR_ETOOBIG = 0, -1, -2, -3, -4, -5, -6
+DEAR_STATIC_MAX_POINTERS, DEAR_STATIC_MAX_TILES = 131072, 98304
 DEAR_F32, DEAR_BF16 = 0, 1
 DEAR_NO_LIMIT = (1 << 63) - 1
 DEAR_SHARD_ALIGN = 32
@@ -22,7 +23,7 @@ DEAR_SHARD_ALIGN = 32
 EXPORTS = [
     "dear_plan", "dear_plan_fixed_layers", "dear_plan_free", "dear_plan_view", "dear_plan_tiles",
     "dear_ctx_create", "dear_ctx_destroy", "dear_ctx_set_max_workgroups",
-    "dear_reduce_scatter", "dear_reduce_scatter_update", "dear_shard_update", "dear_all_gather",
+    "dear_reduce_scatter", "dear_reduce_scatter_static", "dear_reduce_scatter_update", "dear_shard_update", "dear_all_gather",
     "dear_all_gather_workers", "dear_scatter_params", "dear_strerror", "dear_version",
 ]
 
@@ -81,6 +82,7 @@ def load_library() -> C.CDLL:
     lib.dear_ctx_destroy.argtypes = [vp]
     lib.dear_ctx_destroy.restype = None
     lib.dear_reduce_scatter.argtypes = [vp, i32, vp, vp]
+    lib.dear_reduce_scatter_static.argtypes = [vp, i32, C.POINTER(vp), i32, vp, vp]
     lib.dear_shard_update.argtypes = [vp, i32, vp, vp, vp, f32, f32, vp]
     lib.dear_reduce_scatter_update.argtypes = [vp, i32, vp, vp, f32, f32, vp]
     lib.dear_all_gather.argtypes = [vp, i32, vp, vp]
@@ -90,7 +92,7 @@ def load_library() -> C.CDLL:
     lib.dear_strerror.restype = C.c_char_p
     lib.dear_version.restype = C.c_int
     for name in ("dear_plan", "dear_plan_fixed_layers", "dear_plan_view", "dear_plan_tiles", "dear_ctx_create",
-                 "dear_reduce_scatter", "dear_reduce_scatter_update", "dear_shard_update", "dear_all_gather",
+                 "dear_reduce_scatter", "dear_reduce_scatter_static", "dear_reduce_scatter_update", "dear_shard_update", "dear_all_gather",
                  "dear_all_gather_workers", "dear_scatter_params"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
@@ -228,6 +230,17 @@ def _stream(s: Optional[int]) -> C.c_void_p:
 def dear_reduce_scatter(ctx: Context, bucket: int, shard_grad: int, stream: Optional[int] = None) -> None:
     _check(load_library().dear_reduce_scatter(ctx.handle, bucket, C.c_void_p(shard_grad), _stream(stream)),
            "dear_reduce_scatter")
+
+
+def dear_reduce_scatter_static(plan: Plan, grad_dtype: int, grad_ptrs: Sequence[int], bucket: int,
+                               shard_grad: int, stream: Optional[int] = None) -> None:
+    """dear_reduce_scatter without a context and without any allocation (see dear.h)."""
+    n = plan.P * plan.n_layers
+    if len(grad_ptrs) != n:
+        raise ValueError("expected %d pointers, got %d" % (n, len(grad_ptrs)))
+    g = (C.c_void_p * n)(*grad_ptrs)
+    _check(load_library().dear_reduce_scatter_static(plan.handle, grad_dtype, g, bucket, C.c_void_p(shard_grad),
+                                                     _stream(stream)), "dear_reduce_scatter_static")
 
 
 def dear_shard_update(ctx: Context, bucket: int, shard_grad: int, shard_param: int, shard_mom: int,

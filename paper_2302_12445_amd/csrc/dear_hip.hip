@@ -616,22 +616,21 @@ void tile_range(const dear_ctx_impl *c, int32_t bucket, int64_t &first, int64_t 
 
 int launch_status() { return hipGetLastError() == hipSuccess ? DEAR_OK : DEAR_EHIP; }
 
-unsigned grid_width(const dear_ctx_impl *c, int64_t n_items)
+unsigned grid_width(int32_t max_workgroups, int64_t n_items)
 {
-    if (c->max_workgroups > 0 && n_items > c->max_workgroups) return static_cast<unsigned>(c->max_workgroups);
+    if (max_workgroups > 0 && n_items > max_workgroups) return static_cast<unsigned>(max_workgroups);
     return static_cast<unsigned>(n_items);
 }
 
+// tiles, grad_tab: device tables (a context's, or the static scratch's).
 template <bool BF16, bool FUSED>
-void rs_launch(const dear_ctx_impl *c, int64_t n_tiles, hipStream_t st, const dear_tile *tiles,
-               const rs_sink<FUSED> &o)
+void rs_launch(int P, int L, const void *const *grad_tab, int32_t max_workgroups, int64_t n_tiles,
+               hipStream_t st, const dear_tile *tiles, const rs_sink<FUSED> &o)
 {
     constexpr int U = BF16 ? DEAR_RS_U_BF16 : DEAR_RS_U_F32;
     constexpr int SPLIT = DEAR_TILE_ELEMS / ((BF16 ? 8 : 4) * DEAR_BLOCK * U);
-    const int P = c->P, L = c->L;
-    const void *const *grad_tab = c->d_grad;
     const unsigned n_items = static_cast<unsigned>(n_tiles * SPLIT);
-    const dim3 grid(grid_width(c, n_items)), block(DEAR_BLOCK);
+    const dim3 grid(grid_width(max_workgroups, n_items)), block(DEAR_BLOCK);
     const bool bounded = grid.x < n_items;
     const float inv_P = 1.0f / static_cast<float>(P);
 #define RS_LAUNCH(CH, TAIL)                                                                              \
@@ -742,9 +741,9 @@ extern "C" int dear_reduce_scatter(dear_ctx_t *c, int32_t bucket, float *shard_g
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const rs_sink<false> o{shard_grad, nullptr, nullptr, 0.0f, 0.0f};
     if (c->g == 2)
-        rs_launch<true, false>(c, count, st, c->d_tiles + first, o);
+        rs_launch<true, false>(c->P, c->L, c->d_grad, c->max_workgroups, count, st, c->d_tiles + first, o);
     else
-        rs_launch<false, false>(c, count, st, c->d_tiles + first, o);
+        rs_launch<false, false>(c->P, c->L, c->d_grad, c->max_workgroups, count, st, c->d_tiles + first, o);
     return launch_status();
 }
 
@@ -762,9 +761,9 @@ extern "C" int dear_reduce_scatter_update(dear_ctx_t *c, int32_t bucket, float *
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const rs_sink<true> o{nullptr, shard_param, shard_mom, lr, momentum};
     if (c->g == 2)
-        rs_launch<true, true>(c, count, st, c->d_tiles + first, o);
+        rs_launch<true, true>(c->P, c->L, c->d_grad, c->max_workgroups, count, st, c->d_tiles + first, o);
     else
-        rs_launch<false, true>(c, count, st, c->d_tiles + first, o);
+        rs_launch<false, true>(c->P, c->L, c->d_grad, c->max_workgroups, count, st, c->d_tiles + first, o);
     return launch_status();
 }
 
@@ -850,5 +849,98 @@ extern "C" int dear_scatter_params(dear_ctx_t *c, int32_t worker, float *shard_p
     scatter_params_kernel<<<dim3(static_cast<unsigned>(count)), dim3(DEAR_BLOCK), 0,
                             static_cast<hipStream_t>(hip_stream)>>>(c->d_tiles, c->d_param, c->L, worker,
                                                                     shard_param);
+    return launch_status();
+}
+
+// ------------------------------------------------------------- entry point without allocation
+//
+// dear_reduce_scatter needs a context, and creating one allocates device memory for the tile
+// table and the pointer table its kernel reads.  For callers that cannot allocate, the same
+// kernel reads both tables from this file-scope device array instead.  Layout: gradient
+// pointer table first, tile table behind it.  Every GPU the library runs on holds its own copy
+// of the array until the process ends.
+namespace {
+
+constexpr size_t STATIC_MAX_PTRS = DEAR_STATIC_MAX_POINTERS;
+constexpr size_t STATIC_MAX_TILES = DEAR_STATIC_MAX_TILES;
+constexpr size_t STATIC_PTR_BYTES = STATIC_MAX_PTRS * sizeof(void *);
+constexpr size_t STATIC_TILE_BYTES = STATIC_MAX_TILES * sizeof(dear_tile);
+static_assert(STATIC_PTR_BYTES % 256 == 0, "the tile table must start aligned");
+
+__device__ __align__(256) unsigned char scratch[STATIC_PTR_BYTES + STATIC_TILE_BYTES];
+
+// Host staging of the two tables (pageable, file scope: no heap use on this path).
+unsigned char host_stage[STATIC_PTR_BYTES + STATIC_TILE_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+unsigned char *scratch_of_device[MAX_DEVICES];  // device address of `scratch`, per GPU
+
+// `scratch` names a host-side stand-in in host code; the device address has to be asked for,
+// once per device, with that device current.
+int static_scratch(int device, unsigned char **out)
+{
+    if (device < 0 || device >= MAX_DEVICES) return DEAR_EINVAL;
+    if (!scratch_of_device[device]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return DEAR_EHIP;
+        }
+        scratch_of_device[device] = static_cast<unsigned char *>(p);
+    }
+    *out = scratch_of_device[device];
+    return DEAR_OK;
+}
+
+}  // namespace
+
+extern "C" int dear_reduce_scatter_static(const dear_plan_t *plan, int32_t grad_dtype,
+                                          const void *const *grad_ptrs, int32_t bucket, float *shard_grad,
+                                          void *hip_stream)
+{
+    if (!plan || !grad_ptrs) return DEAR_EINVAL;
+    if (grad_dtype != DEAR_F32 && grad_dtype != DEAR_BF16) return DEAR_EINVAL;
+    if ((grad_dtype == DEAR_F32 ? 4 : 2) != plan->g) return DEAR_EINVAL;
+    if (bucket < -1 || bucket >= plan->B) return DEAR_ERANGE;
+    int rc = check_shard_buffer(shard_grad);
+    if (rc != DEAR_OK) return rc;
+    const size_t n_ptr = static_cast<size_t>(plan->P) * plan->L;
+    if (n_ptr > STATIC_MAX_PTRS) return DEAR_ETOOBIG;
+    const int32_t b_first = bucket < 0 ? 0 : bucket, b_last = bucket < 0 ? plan->B : bucket + 1;
+    // only the gradient tensors of the buckets processed are dereferenced, but the whole table is checked
+    for (size_t i = 0; i < n_ptr; ++i) {
+        if (!grad_ptrs[i]) return DEAR_EINVAL;
+        if (misaligned(grad_ptrs[i], 16)) return DEAR_EALIGN;
+    }
+    dear_tile *host_tiles = reinterpret_cast<dear_tile *>(host_stage + STATIC_PTR_BYTES);
+    const int64_t n_tiles = dear_emit_tiles(*plan, b_first, b_last, host_tiles, STATIC_MAX_TILES, nullptr);
+    if (n_tiles > static_cast<int64_t>(STATIC_MAX_TILES)) return DEAR_ETOOBIG;
+    if (n_tiles == 0) return DEAR_OK;
+
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess) return DEAR_EHIP;
+    unsigned char *dev = nullptr;
+    rc = static_scratch(device, &dev);
+    if (rc != DEAR_OK) return rc;
+
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    for (size_t i = 0; i < n_ptr; ++i) reinterpret_cast<const void **>(host_stage)[i] = grad_ptrs[i];
+    // Stream-ordered uploads: earlier kernels of this stream that still read the scratch finish
+    // first.  The staging memory is pageable and is reused by the next call, so the stream is
+    // drained before returning to the point where the copies have been taken.
+    if (hipMemcpyAsync(dev, host_stage, n_ptr * sizeof(void *), hipMemcpyHostToDevice, st) != hipSuccess ||
+        hipMemcpyAsync(dev + STATIC_PTR_BYTES, host_tiles, static_cast<size_t>(n_tiles) * sizeof(dear_tile),
+                       hipMemcpyHostToDevice, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess) {
+        (void)hipGetLastError();
+        return DEAR_EHIP;
+    }
+    const void *const *grad_tab = reinterpret_cast<const void *const *>(dev);
+    const dear_tile *tiles = reinterpret_cast<const dear_tile *>(dev + STATIC_PTR_BYTES);
+    const rs_sink<false> o{shard_grad, nullptr, nullptr, 0.0f, 0.0f};
+    if (plan->g == 2)
+        rs_launch<true, false>(plan->P, plan->L, grad_tab, 0, n_tiles, st, tiles, o);
+    else
+        rs_launch<false, false>(plan->P, plan->L, grad_tab, 0, n_tiles, st, tiles, o);
     return launch_status();
 }

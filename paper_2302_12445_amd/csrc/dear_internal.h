@@ -23,4 +23,6 @@ static_assert(sizeof(dear_tile) == 32, "tile descriptors are read as two 16-byte
 constexpr int DEAR_BLOCK = 256;  // threads per workgroup = 4 wavefronts
 
 // Cuts every bucket of the plan into tiles (plan.cpp).
+int64_t dear_emit_tiles(const dear_plan_s &pl, int32_t b_first, int32_t b_last, dear_tile *out,
+                        int64_t capacity, int64_t *tile_begin);
 void dear_build_tiles(const dear_plan_s &pl, std::vector<dear_tile> &tiles, std::vector<int64_t> &tile_begin);

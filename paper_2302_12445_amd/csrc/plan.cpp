@@ -120,14 +120,22 @@ extern "C" int dear_plan_fixed_layers(const int64_t *layer_sizes, int32_t n_laye
     return DEAR_OK;
 }
 
-// Cut every bucket into tiles: runs of one layer within one shard, split at multiples of
-// DEAR_TILE_ELEMS of the layer's own element index so that tile-interior vectors stay
-// aligned; then the padding slots behind the last real element.
-void dear_build_tiles(const dear_plan_s &pl, std::vector<dear_tile> &tiles, std::vector<int64_t> &tile_begin)
+// Cut the buckets b_first .. b_last-1 into tiles: runs of one layer within one shard, split
+// at multiples of DEAR_TILE_ELEMS of the layer's own element index so that tile-interior
+// vectors stay aligned; then the padding slots behind the last real element.  Tiles are
+// written to out[0 .. capacity) as far as they fit; the return value is the number of tiles
+// the buckets have (so a first call with capacity 0 sizes the table).  tile_begin, if given,
+// receives b_last - b_first + 1 range starts relative to the first tile written.
+int64_t dear_emit_tiles(const dear_plan_s &pl, int32_t b_first, int32_t b_last, dear_tile *out,
+                        int64_t capacity, int64_t *tile_begin)
 {
-    tile_begin.assign(pl.B + 1, 0);
-    for (int32_t b = 0; b < pl.B; ++b) {
-        tile_begin[b] = static_cast<int64_t>(tiles.size());
+    int64_t n_out = 0;
+    auto emit = [&](const dear_tile &t) {
+        if (n_out < capacity) out[n_out] = t;
+        ++n_out;
+    };
+    for (int32_t b = b_first; b < b_last; ++b) {
+        if (tile_begin) tile_begin[b - b_first] = n_out;
         const int64_t S = pl.bucket_shard_len[b], base = pl.bucket_shard_base[b];
         const int32_t lo = pl.bucket_first_layer[b], hi = lo + pl.bucket_n_layers[b];
         for (int32_t l = hi - 1; l >= lo; --l) {
@@ -146,7 +154,7 @@ void dear_build_tiles(const dear_plan_s &pl, std::vector<dear_tile> &tiles, std:
                     t.layer = l;
                     t.shard = static_cast<int32_t>(s);
                     t.bucket = b;
-                    tiles.push_back(t);
+                    emit(t);
                     i = end;
                 }
             }
@@ -164,11 +172,20 @@ void dear_build_tiles(const dear_plan_s &pl, std::vector<dear_tile> &tiles, std:
             t.layer = -1;
             t.shard = static_cast<int32_t>(s);
             t.bucket = b;
-            tiles.push_back(t);
+            emit(t);
             e = end;
         }
     }
-    tile_begin[pl.B] = static_cast<int64_t>(tiles.size());
+    if (tile_begin) tile_begin[b_last - b_first] = n_out;
+    return n_out;
+}
+
+void dear_build_tiles(const dear_plan_s &pl, std::vector<dear_tile> &tiles, std::vector<int64_t> &tile_begin)
+{
+    tile_begin.assign(pl.B + 1, 0);
+    const int64_t n = dear_emit_tiles(pl, 0, pl.B, nullptr, 0, nullptr);
+    tiles.resize(static_cast<size_t>(n));
+    dear_emit_tiles(pl, 0, pl.B, tiles.data(), n, tile_begin.data());
 }
 
 extern "C" int dear_plan_tiles(const dear_plan_t *plan, dear_tile_t *out, int64_t capacity,
@@ -224,8 +241,9 @@ extern "C" const char *dear_strerror(int status)
     case DEAR_EHIP: return "HIP runtime error";
     case DEAR_ERANGE: return "bucket or worker index out of range";
     case DEAR_EALIGN: return "device pointer not aligned as required";
+    case DEAR_ETOOBIG: return "input exceeds the capacity of the static device scratch";
     default: return "unknown status";
     }
 }
 
-extern "C" int dear_version(void) { return 100; }
+extern "C" int dear_version(void) { return 200; }
