@@ -167,13 +167,21 @@ void dear_ctx_destroy(dear_ctx_t *ctx); /* NULL is ignored; synchronises the dev
 /* dear_ctx_set_max_workgroups -- bound the grid of the kernels launched through this
  * context.  0 (the default) gives every work item its own workgroup, which is fastest
  * when the aggregation has the GPU to itself.  A positive bound (a few hundred; 256 =
- * one per compute unit) makes each workgroup stride over the items at a raised wave
- * priority; this is meant for the DeAR schedule on one GPU (paper Section III-B), where
+ * one per compute unit) makes each workgroup stride over the items; this is meant for the DeAR schedule on one GPU (paper Section III-B), where
  * the reduce-scatter runs beside back-propagation kernels and the all-gather beside
  * feed-forward kernels: a bounded grid disturbs the compute kernels far less.  Results
  * are identical for every setting.  Takes effect for calls made afterwards.
  * Errors: DEAR_EINVAL (null context, negative bound). */
 int dear_ctx_set_max_workgroups(dear_ctx_t *ctx, int32_t max_workgroups);
+
+/* dear_ctx_set_wave_priority -- wave priority (0..3, default 0) of the kernels launched with
+ * a bounded grid through this context (it has no effect on unbounded launches).  A raised
+ * priority lets the aggregation's wavefronts win instruction issue against the wavefronts
+ * of a compute kernel on the same compute unit: the aggregation finishes sooner, the
+ * compute kernel is slowed more.  Which setting hides more depends on how much slack the
+ * schedule leaves the aggregation.  Results are identical for every setting.
+ * Errors: DEAR_EINVAL (null context, priority outside 0..3). */
+int dear_ctx_set_wave_priority(dear_ctx_t *ctx, int32_t priority);
 
 /* Shard buffers (arguments shard_grad, shard_param, shard_mom below): DEVICE, fp32,
  * P rows of total_shard_len elements, row stride total_shard_len, base 256-byte

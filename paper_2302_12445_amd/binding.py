@@ -22,7 +22,7 @@ DEAR_SHARD_ALIGN = 32
 
 EXPORTS = [
     "dear_plan", "dear_plan_fixed_layers", "dear_plan_free", "dear_plan_view", "dear_plan_tiles",
-    "dear_ctx_create", "dear_ctx_destroy", "dear_ctx_set_max_workgroups",
+    "dear_ctx_create", "dear_ctx_destroy", "dear_ctx_set_max_workgroups", "dear_ctx_set_wave_priority",
     "dear_reduce_scatter", "dear_reduce_scatter_static", "dear_reduce_scatter_update", "dear_shard_update", "dear_all_gather",
     "dear_all_gather_workers", "dear_scatter_params", "dear_strerror", "dear_version",
 ]
@@ -79,6 +79,8 @@ def load_library() -> C.CDLL:
     lib.dear_ctx_create.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp)]
     lib.dear_ctx_set_max_workgroups.argtypes = [vp, i32]
     lib.dear_ctx_set_max_workgroups.restype = C.c_int
+    lib.dear_ctx_set_wave_priority.argtypes = [vp, i32]
+    lib.dear_ctx_set_wave_priority.restype = C.c_int
     lib.dear_ctx_destroy.argtypes = [vp]
     lib.dear_ctx_destroy.restype = None
     lib.dear_reduce_scatter.argtypes = [vp, i32, vp, vp]
@@ -221,6 +223,10 @@ def dear_ctx_create(plan: Plan, grad_dtype: int, grad_ptrs: Sequence[int],
 
 def dear_ctx_set_max_workgroups(ctx: Context, max_workgroups: int) -> None:
     _check(load_library().dear_ctx_set_max_workgroups(ctx.handle, max_workgroups), "dear_ctx_set_max_workgroups")
+
+
+def dear_ctx_set_wave_priority(ctx: Context, priority: int) -> None:
+    _check(load_library().dear_ctx_set_wave_priority(ctx.handle, priority), "dear_ctx_set_wave_priority")
 
 
 def _stream(s: Optional[int]) -> C.c_void_p:

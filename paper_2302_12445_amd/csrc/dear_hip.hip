@@ -37,6 +37,7 @@ struct dear_ctx_impl {
     int32_t L = 0, B = 0, P = 0, g = 0;
     int device = 0;
     int32_t max_workgroups = 0;  // 0: one workgroup per work item
+    int32_t wave_priority = 0;   // wave priority (0..3) of bounded-grid kernels
     int64_t row_len = 0;
     std::vector<int64_t> bucket_shard_len, bucket_shard_base;
     std::vector<int64_t> tile_begin;  // [B+1] range of bucket b's tiles in the tile table
@@ -69,7 +70,7 @@ struct dear_ctx_impl {
 #define DEAR_AG_NT_LOAD 0
 #endif
 #ifndef DEAR_AG_CHUNK_BYTES
-#define DEAR_AG_CHUNK_BYTES (8 << 20)  // shard bytes whose P copies are written back to back
+#define DEAR_AG_CHUNK_BYTES (16 << 20)  // shard bytes whose P copies are written back to back
 #endif
 #ifndef DEAR_AG_NT_STORE
 #define DEAR_AG_NT_STORE 1
@@ -165,15 +166,21 @@ __device__ __forceinline__ void add_vector(float (&acc)[VE], const u4 r)
 // grid (dear_ctx_set_max_workgroups): BOUNDED = true, each workgroup strides over the items.
 // That is for running beside compute kernels on the same GPU: a few hundred resident
 // workgroups with many loads in flight each disturb a GEMM's memory latency far less than
-// a full grid, and a raised wave priority keeps these few wavefronts from being starved
-// of issue slots by an MFMA-saturated neighbour.
+// a full grid.  `prio` (dear_ctx_set_wave_priority) raises the wave priority of such a
+// kernel: its wavefronts then win instruction issue against an MFMA-saturated neighbour,
+// which makes the aggregation faster and the neighbour slower.
 template <bool BOUNDED, class Body>
-__device__ __forceinline__ void for_each_item(unsigned n_items, Body body)
+__device__ __forceinline__ void for_each_item(unsigned n_items, int prio, Body body)
 {
     if (!BOUNDED) {
         body(blockIdx.x);
     } else {
-        __builtin_amdgcn_s_setprio(3);
+        if (prio == 1)
+            __builtin_amdgcn_s_setprio(1);
+        else if (prio == 2)
+            __builtin_amdgcn_s_setprio(2);
+        else if (prio == 3)
+            __builtin_amdgcn_s_setprio(3);
         for (unsigned item = blockIdx.x; item < n_items; item += gridDim.x) body(item);
     }
 }
@@ -356,11 +363,11 @@ __device__ __forceinline__ void reduce_scatter_tile(const dear_tile &t, int part
 template <bool BF16, int U, int CH, bool TAIL, bool FUSED, bool BOUNDED>
 __global__ __launch_bounds__(DEAR_BLOCK) void reduce_scatter_kernel(
     const dear_tile *__restrict__ tiles, const void *const *__restrict__ grad_tab, int L, int P,
-    float inv_P, const rs_sink<FUSED> o, unsigned n_items)
+    float inv_P, const rs_sink<FUSED> o, unsigned n_items, int prio)
 {
     constexpr int SPLIT = DEAR_TILE_ELEMS / ((BF16 ? 8 : 4) * DEAR_BLOCK * U);
     static_assert(SPLIT >= 1 && (SPLIT & (SPLIT - 1)) == 0, "U must divide the tile");
-    for_each_item<BOUNDED>(n_items, [&](unsigned item) {
+    for_each_item<BOUNDED>(n_items, prio, [&](unsigned item) {
         const dear_tile t = tiles[item / SPLIT];
         const int part = item % SPLIT;
         if (t.layer < 0) {  // padding slots: gbar = +0
@@ -381,9 +388,9 @@ constexpr int UPD_U_BOUNDED = 4;       // bounded grid: more loads in flight per
 template <int U, bool BOUNDED>
 __global__ __launch_bounds__(DEAR_BLOCK) void shard_update_kernel(
     const float *__restrict__ g, float *__restrict__ w, float *__restrict__ v, int64_t row_stride,
-    int64_t base, int64_t vecs, float lr, float mu, unsigned blocks_per_row, unsigned n_items)
+    int64_t base, int64_t vecs, float lr, float mu, unsigned blocks_per_row, unsigned n_items, int prio)
 {
-    for_each_item<BOUNDED>(n_items, [&](unsigned item) {
+    for_each_item<BOUNDED>(n_items, prio, [&](unsigned item) {
         const unsigned row = item / blocks_per_row, bx = item - row * blocks_per_row;
         const int64_t off = (int64_t)row * row_stride + base;
         const f4 *__restrict__ g4 = reinterpret_cast<const f4 *>(g + off);
@@ -472,7 +479,7 @@ __global__ __launch_bounds__(DEAR_BLOCK) void all_gather_kernel(
     static_assert(SPLIT >= 1 && (SPLIT & (SPLIT - 1)) == 0, "U must divide the tile");
     constexpr unsigned CHUNK = DEAR_AG_CHUNK_BYTES / (16 * DEAR_BLOCK * U);  // parts per chunk
     const unsigned per_chunk = CHUNK * (unsigned)n_p;
-    for_each_item<BOUNDED>(n_items, [&](unsigned item) {
+    for_each_item<BOUNDED>(n_items, 0, [&](unsigned item) {
         // item -> (chunk, replica, part within chunk); the last chunk may be short
         const unsigned chunk = item / per_chunk;
         const unsigned r = item - chunk * per_chunk;
@@ -537,9 +544,9 @@ __device__ __forceinline__ void all_gather_tile_all_replicas(const dear_tile &t,
 
 __global__ __launch_bounds__(DEAR_BLOCK) void all_gather_bounded_kernel(
     const dear_tile *__restrict__ tiles, float *const *__restrict__ param_tab, int L, int p_first,
-    int n_p, const float *__restrict__ shard_param, unsigned n_tiles)
+    int n_p, const float *__restrict__ shard_param, unsigned n_tiles, int prio)
 {
-    for_each_item<true>(n_tiles, [&](unsigned item) {
+    for_each_item<true>(n_tiles, prio, [&](unsigned item) {
         const dear_tile t = tiles[item];
         if (t.layer < 0) return;
         const float *__restrict__ src = shard_param + t.dst_begin;
@@ -624,7 +631,7 @@ unsigned grid_width(int32_t max_workgroups, int64_t n_items)
 
 // tiles, grad_tab: device tables (a context's, or the static scratch's).
 template <bool BF16, bool FUSED>
-void rs_launch(int P, int L, const void *const *grad_tab, int32_t max_workgroups, int64_t n_tiles,
+void rs_launch(int P, int L, const void *const *grad_tab, int32_t max_workgroups, int prio, int64_t n_tiles,
                hipStream_t st, const dear_tile *tiles, const rs_sink<FUSED> &o)
 {
     constexpr int U = BF16 ? DEAR_RS_U_BF16 : DEAR_RS_U_F32;
@@ -637,10 +644,10 @@ void rs_launch(int P, int L, const void *const *grad_tab, int32_t max_workgroups
     do {                                                                                                 \
         if (bounded)                                                                                     \
             reduce_scatter_kernel<BF16, U, CH, TAIL, FUSED, true><<<grid, block, 0, st>>>(              \
-                tiles, grad_tab, L, P, inv_P, o, n_items);                                               \
+                tiles, grad_tab, L, P, inv_P, o, n_items, prio);                                         \
         else                                                                                             \
             reduce_scatter_kernel<BF16, U, CH, TAIL, FUSED, false><<<grid, block, 0, st>>>(             \
-                tiles, grad_tab, L, P, inv_P, o, n_items);                                               \
+                tiles, grad_tab, L, P, inv_P, o, n_items, 0);                                            \
     } while (0)
     // replicas per load batch: the largest of 8/4/2/1 that divides P without a tail when
     // P is small or a multiple of 4; otherwise batches of 8 with a predicated tail
@@ -720,6 +727,13 @@ extern "C" int dear_ctx_set_max_workgroups(dear_ctx_t *c, int32_t max_workgroups
     return DEAR_OK;
 }
 
+extern "C" int dear_ctx_set_wave_priority(dear_ctx_t *c, int32_t priority)
+{
+    if (!c || priority < 0 || priority > 3) return DEAR_EINVAL;
+    c->wave_priority = priority;
+    return DEAR_OK;
+}
+
 extern "C" void dear_ctx_destroy(dear_ctx_t *c)
 {
     if (!c) return;
@@ -741,9 +755,9 @@ extern "C" int dear_reduce_scatter(dear_ctx_t *c, int32_t bucket, float *shard_g
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const rs_sink<false> o{shard_grad, nullptr, nullptr, 0.0f, 0.0f};
     if (c->g == 2)
-        rs_launch<true, false>(c->P, c->L, c->d_grad, c->max_workgroups, count, st, c->d_tiles + first, o);
+        rs_launch<true, false>(c->P, c->L, c->d_grad, c->max_workgroups, c->wave_priority, count, st, c->d_tiles + first, o);
     else
-        rs_launch<false, false>(c->P, c->L, c->d_grad, c->max_workgroups, count, st, c->d_tiles + first, o);
+        rs_launch<false, false>(c->P, c->L, c->d_grad, c->max_workgroups, c->wave_priority, count, st, c->d_tiles + first, o);
     return launch_status();
 }
 
@@ -761,9 +775,9 @@ extern "C" int dear_reduce_scatter_update(dear_ctx_t *c, int32_t bucket, float *
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const rs_sink<true> o{nullptr, shard_param, shard_mom, lr, momentum};
     if (c->g == 2)
-        rs_launch<true, true>(c->P, c->L, c->d_grad, c->max_workgroups, count, st, c->d_tiles + first, o);
+        rs_launch<true, true>(c->P, c->L, c->d_grad, c->max_workgroups, c->wave_priority, count, st, c->d_tiles + first, o);
     else
-        rs_launch<false, true>(c->P, c->L, c->d_grad, c->max_workgroups, count, st, c->d_tiles + first, o);
+        rs_launch<false, true>(c->P, c->L, c->d_grad, c->max_workgroups, c->wave_priority, count, st, c->d_tiles + first, o);
     return launch_status();
 }
 
@@ -797,11 +811,11 @@ extern "C" int dear_shard_update(dear_ctx_t *c, int32_t bucket, const float *sha
     if (bounded)
         shard_update_kernel<UPD_U_BOUNDED, true><<<dim3(c->max_workgroups), dim3(DEAR_BLOCK), 0, st>>>(
             shard_grad, shard_param, shard_mom, c->row_len, base, vecs, lr, momentum,
-            static_cast<unsigned>(blocks), static_cast<unsigned>(n_items));
+            static_cast<unsigned>(blocks), static_cast<unsigned>(n_items), c->wave_priority);
     else
         shard_update_kernel<UPD_U, false><<<dim3(static_cast<unsigned>(n_items)), dim3(DEAR_BLOCK), 0, st>>>(
             shard_grad, shard_param, shard_mom, c->row_len, base, vecs, lr, momentum,
-            static_cast<unsigned>(blocks), static_cast<unsigned>(n_items));
+            static_cast<unsigned>(blocks), static_cast<unsigned>(n_items), 0);
     return launch_status();
 }
 
@@ -818,10 +832,12 @@ extern "C" int dear_all_gather_workers(dear_ctx_t *c, int32_t bucket, const floa
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     constexpr int64_t split_free = DEAR_TILE_ELEMS / (4 * DEAR_BLOCK * AG_U);
     if (count * split_free * n_workers > 0x7fffffff) return DEAR_EINVAL;
-    if (c->max_workgroups > 0 && count > c->max_workgroups) {
-        all_gather_bounded_kernel<<<dim3(c->max_workgroups), dim3(DEAR_BLOCK), 0, st>>>(
+    if (c->max_workgroups > 0 && count * split_free * n_workers > c->max_workgroups) {
+        // the bounded form strides over whole tiles, so its grid is at most the tile count
+        const unsigned width = grid_width(c->max_workgroups, count);
+        all_gather_bounded_kernel<<<dim3(width), dim3(DEAR_BLOCK), 0, st>>>(
             c->d_tiles + first, c->d_param, c->L, first_worker, n_workers, shard_param,
-            static_cast<unsigned>(count));
+            static_cast<unsigned>(count), c->wave_priority);
     } else {
         const int64_t n_parts = count * split_free, n_items = n_parts * n_workers;
         all_gather_kernel<AG_U, false><<<dim3(static_cast<unsigned>(n_items)), dim3(DEAR_BLOCK), 0, st>>>(
@@ -939,8 +955,8 @@ extern "C" int dear_reduce_scatter_static(const dear_plan_t *plan, int32_t grad_
     const dear_tile *tiles = reinterpret_cast<const dear_tile *>(dev + STATIC_PTR_BYTES);
     const rs_sink<false> o{shard_grad, nullptr, nullptr, 0.0f, 0.0f};
     if (plan->g == 2)
-        rs_launch<true, false>(plan->P, plan->L, grad_tab, 0, n_tiles, st, tiles, o);
+        rs_launch<true, false>(plan->P, plan->L, grad_tab, 0, 0, n_tiles, st, tiles, o);
     else
-        rs_launch<false, false>(plan->P, plan->L, grad_tab, 0, n_tiles, st, tiles, o);
+        rs_launch<false, false>(plan->P, plan->L, grad_tab, 0, 0, n_tiles, st, tiles, o);
     return launch_status();
 }

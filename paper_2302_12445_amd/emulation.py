@@ -146,6 +146,7 @@ class EmulatedWorkers:
         self.ctx.destroy()
         self.ctx, self.plan = new_ctx, new_plan
         B.dear_ctx_set_max_workgroups(self.ctx, getattr(self, "max_workgroups", 0))
+        B.dear_ctx_set_wave_priority(self.ctx, getattr(self, "wave_priority", 0))
         self.shard_grad, self.shard_param, self.shard_mom = new_grad, new_param, new_mom
 
     def capture_iteration(self, lr: float, momentum: float, per_bucket: bool = True,
@@ -166,6 +167,11 @@ class EmulatedWorkers:
         """0: one workgroup per work item (default); n > 0: bounded grid for running beside compute."""
         self.max_workgroups = n
         B.dear_ctx_set_max_workgroups(self.ctx, n)
+
+    def set_wave_priority(self, priority: int) -> None:
+        """Wave priority (0..3) of bounded-grid launches."""
+        self.wave_priority = priority
+        B.dear_ctx_set_wave_priority(self.ctx, priority)
 
     def close(self) -> None:
         self.ctx.destroy()

@@ -26,15 +26,37 @@ import torch
 from .emulation import EmulatedWorkers
 
 
+def streams_run_concurrently(busy: torch.cuda.Stream, other: torch.cuda.Stream, work: Callable[[], None],
+                             probe: torch.Tensor) -> bool:
+    """True if a kernel queued on `other` completes while `busy` is still working.  HIP maps
+    its streams onto a few hardware queues; two streams that land on the same queue run
+    strictly one after the other, and a schedule built on them cannot overlap anything."""
+    torch.cuda.synchronize()
+    with torch.cuda.stream(busy):
+        for _ in range(4):
+            work()
+        busy_done = torch.cuda.Event()
+        busy_done.record(busy)
+    with torch.cuda.stream(other):
+        probe.zero_()
+        other_done = torch.cuda.Event()
+        other_done.record(other)
+    other_done.synchronize()
+    concurrent = not busy_done.query()
+    busy.synchronize()
+    return concurrent
+
+
 class DearSchedule:
     MODES = ("dear", "wfbp", "serial", "compute_only", "comm_only")
 
     def __init__(self, em: EmulatedWorkers, lr: float, momentum: float, gemm_dim: int = 4096,
                  ff_gemms: int = 1, bp_gemms: int = 2,
                  on_backward: Optional[Callable[[int, int], None]] = None,
-                 overlap_workgroups: int = 256, overlap_workgroups_ag: Optional[int] = 192,
-                 fused_update: bool = False, gemm_dtype: torch.dtype = torch.float32,
-                 full_width_when_alone: bool = False,
+                 overlap_workgroups: int = 256, overlap_workgroups_ag: Optional[int] = 256,
+                 fused_update: bool = True, gemm_dtype: torch.dtype = torch.float32,
+                 full_width_when_alone: bool = True,
+                 wave_priority: int = 3, wave_priority_ag: Optional[int] = 0,
                  compute_stream: Optional[torch.cuda.Stream] = None,
                  comm_stream: Optional[torch.cuda.Stream] = None):
         """on_backward(iteration, bucket) runs on the compute stream behind the bucket's
@@ -42,14 +64,21 @@ class DearSchedule:
         overlap_workgroups bounds the grid of the aggregation kernels in the overlapping
         modes (dear, wfbp); 0 leaves them unbounded.  overlap_workgroups_ag, if given, is
         the bound for the all-gather (the forward pass it hides under is half as long as
-        the backward pass, so it may need a wider grid).
+        the backward pass).  The defaults are what hid most on an MI355X beside fp32 4096^3
+        GEMMs: 256 workgroups for both, reduce-scatter at wave priority 3 (it has many
+        instructions per byte and little slack under two GEMMs), all-gather at priority 0 (it
+        has few and the whole forward pass to finish in).
         fused_update: reduce-scatter and update of a bucket in one kernel (fewer bytes).
+        wave_priority / wave_priority_ag: wave priority (0..3) of the bounded reduce-scatter /
+        update and of the bounded all-gather.
         full_width_when_alone: in mode dear, the kernels that can have no compute beside
         them (the last bucket's reduce-scatter/update after the backward pass has ended,
         and the first all-gather the forward pass waits for) run with an unbounded grid."""
         self.em, self.lr, self.momentum = em, lr, momentum
         self.fused_update = fused_update
         self.full_width_when_alone = full_width_when_alone
+        self.wave_priority = wave_priority
+        self.wave_priority_ag = wave_priority if wave_priority_ag is None else wave_priority_ag
         self.overlap_workgroups = overlap_workgroups
         self.overlap_workgroups_ag = overlap_workgroups if overlap_workgroups_ag is None else overlap_workgroups_ag
         if overlap_workgroups == 0:
@@ -58,11 +87,26 @@ class DearSchedule:
         self.ff_gemms, self.bp_gemms = ff_gemms, bp_gemms
         self.on_backward = on_backward
         dev = em.device
-        self.compute = compute_stream if compute_stream is not None else torch.cuda.Stream(device=dev)
-        self.comm = comm_stream if comm_stream is not None else torch.cuda.Stream(device=dev)
         self.a = torch.randn(gemm_dim, gemm_dim, device=dev, dtype=torch.float32).to(gemm_dtype)
         self.b = torch.randn(gemm_dim, gemm_dim, device=dev, dtype=torch.float32).to(gemm_dtype)
         self.c = torch.empty(gemm_dim, gemm_dim, device=dev, dtype=gemm_dtype)
+        self.compute = compute_stream if compute_stream is not None else torch.cuda.Stream(device=dev)
+        self.comm = comm_stream
+        self.streams_concurrent = True
+        if self.comm is None:
+            # take the first stream that really runs beside the compute stream (different hardware queue)
+            probe = torch.zeros(64, device=dev)
+            m = torch.zeros(4096, 4096, device=dev)       # about a millisecond of work per product
+            tried = []
+            for _ in range(8):
+                cand = torch.cuda.Stream(device=dev)
+                tried.append(cand)
+                if streams_run_concurrently(self.compute, cand, lambda: torch.matmul(m, m), probe):
+                    self.comm = cand
+                    break
+            del m
+            if self.comm is None:
+                self.comm, self.streams_concurrent = tried[0], False
         self.grad_ready = [torch.cuda.Event() for _ in range(self.nb)]
         self.rs_done = [torch.cuda.Event() for _ in range(self.nb)]
         self.ag_done = [torch.cuda.Event() for _ in range(self.nb)]
@@ -110,6 +154,7 @@ class DearSchedule:
         w_rs = self.overlap_workgroups if overlapping else 0
         w_ag = self.overlap_workgroups_ag if overlapping else 0
         em.set_max_workgroups(w_rs)
+        em.set_wave_priority(self.wave_priority)
         if mode == "compute_only":
             self._forward(False)
             self._backward(False)
@@ -136,9 +181,11 @@ class DearSchedule:
             for b in range(nb):
                 self.comm.wait_event(self.grad_ready[b])
                 em.set_max_workgroups(w_rs)
+                em.set_wave_priority(self.wave_priority)
                 self._reduce_scatter_and_update(b, self.comm)
                 self.rs_done[b].record(self.comm)
                 em.set_max_workgroups(w_ag)
+                em.set_wave_priority(self.wave_priority_ag)
                 em.all_gather(b, self.comm)
             self.ag_done[nb - 1].record(self.comm)
             for b in range(nb - 1):
@@ -159,6 +206,7 @@ class DearSchedule:
                 self.rs_done[b].record(self.comm)
             # all OP1 precede every OP2: in order on the one communication stream.
             # OP2 in forward order, to be hidden under the next forward pass
+            em.set_wave_priority(self.wave_priority_ag)
             for b in reversed(range(nb)):
                 em.set_max_workgroups(0 if (alone and b == nb - 1) else w_ag)   # the forward pass waits for the first
                 em.all_gather(b, self.comm)
@@ -201,6 +249,7 @@ class DearSchedule:
             torch.cuda.synchronize()
             return (time.perf_counter() - t0) * 1e3 / iterations
 
+        self.em.set_max_workgroups(0)   # every part alone, at full width
         out["ff"] = timed(lambda: self._forward(False))
         out["bp"] = timed(lambda: self._backward(False))
         out["rs"] = timed(lambda: [self._reduce_scatter_and_update(b, self.comm) for b in range(self.nb)])
@@ -217,6 +266,7 @@ def overlap_report(sched: DearSchedule, iterations: int = 10) -> Dict[str, objec
     ideal_dear = max(ph["ff"], ph["ag"]) + max(ph["bp"], ph["rs"])      # paper Sec. VI-I
     ideal_base = ph["ff"] + max(ph["bp"], ph["rs"] + ph["ag"])
     return {
+        "streams_concurrent": sched.streams_concurrent,
         "phases_ms": {k: round(v, 4) for k, v in ph.items()},
         "iteration_ms": {k: round(v, 4) for k, v in t.items()},
         "hidden_fraction_dear": round(hidden, 4), "hidden_fraction_wfbp": round(hidden_wfbp, 4),

@@ -35,8 +35,12 @@ def main() -> None:
     ap.add_argument("--iterations", type=int, default=10)
     ap.add_argument("--overlap-workgroups", type=int, default=256,
                     help="grid bound of reduce-scatter/update while they overlap compute (0 = unbounded)")
-    ap.add_argument("--overlap-workgroups-ag", type=int, default=192,
+    ap.add_argument("--overlap-workgroups-ag", type=int, default=256,
                     help="grid bound of the all-gather while it overlaps compute")
+    ap.add_argument("--wave-priority", type=int, default=3, help="wave priority of bounded reduce-scatter/update")
+    ap.add_argument("--wave-priority-ag", type=int, default=0, help="wave priority of the bounded all-gather")
+    ap.add_argument("--unfused", action="store_true", help="reduce-scatter and update as two kernels")
+    ap.add_argument("--gemm-dtype", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--trace-iterations", type=int, default=0,
                     help="after the report, run this many DeAR iterations only (for a kernel trace)")
     args = ap.parse_args()
@@ -56,14 +60,21 @@ def main() -> None:
 
     sched = DearSchedule(em, w.lr, w.momentum, args.gemm_dim, args.ff_gemms, args.bp_gemms,
                          overlap_workgroups=args.overlap_workgroups,
-                         overlap_workgroups_ag=args.overlap_workgroups_ag)
+                         overlap_workgroups_ag=args.overlap_workgroups_ag,
+                         fused_update=not args.unfused,
+                         gemm_dtype=torch.float32 if args.gemm_dtype == "f32" else torch.bfloat16,
+                         wave_priority=args.wave_priority, wave_priority_ag=args.wave_priority_ag)
     rep = overlap_report(sched, args.iterations)
     rep["config"] = {"workload": w.name, "P": w.P, "buckets": em.plan.n_buckets, "gemm_dim": args.gemm_dim,
                      "ff_gemms_per_bucket": args.ff_gemms, "bp_gemms_per_bucket": args.bp_gemms,
-                     "gemm_dtype": "f32", "overlap_workgroups": [args.overlap_workgroups, args.overlap_workgroups_ag]}
+                     "gemm_dtype": args.gemm_dtype, "fused_update": not args.unfused,
+                     "overlap_workgroups": [args.overlap_workgroups, args.overlap_workgroups_ag],
+                     "wave_priority": [args.wave_priority, args.wave_priority_ag]}
     print(json.dumps(rep), flush=True)
     for _ in range(args.trace_iterations):
         sched.iteration("dear")
+    if args.trace_iterations:
+        sched._forward(True)   # the forward pass the last iteration's all-gathers run under
     sched.synchronize()
     em.close()
 

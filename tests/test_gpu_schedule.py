@@ -15,11 +15,12 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
+@pytest.mark.parametrize("fused", [True, False])
 @pytest.mark.parametrize("mode", ["dear", "wfbp", "serial"])
-def test_schedule_matches_oracle(mode):
+def test_schedule_matches_oracle(mode, fused):
     from paper_2302_12445_amd.emulation import EmulatedWorkers
     from paper_2302_12445_amd.schedule import DearSchedule
-    print("case: schedule parity, mode", mode, flush=True)
+    print("case: schedule parity, mode", mode, "fused update" if fused else "separate update", flush=True)
     sizes = [4097, 3, 8191, 4096, 1, 12289, 7, 30001, 64, 513, 70000, 9]
     w = small_workload(sizes, 4, 30000 * 4, "f32", index=81)
     em = EmulatedWorkers(w.sizes, w.P, w.grad_dtype, w.threshold_bytes, DEV)
@@ -47,7 +48,7 @@ def test_schedule_matches_oracle(mode):
     torch.cuda.synchronize()
 
     sched = DearSchedule(em, w.lr, w.momentum, gemm_dim=512, ff_gemms=1, bp_gemms=2, on_backward=on_backward,
-                         overlap_workgroups=8)
+                         overlap_workgroups=8, overlap_workgroups_ag=5, fused_update=fused)
     for it in range(iters):
         sched.iteration(mode)
     sched.synchronize()
