@@ -2,21 +2,30 @@
 """Benchmark of the DeAR gradient-aggregation path on one MI355X.
 
 One step = one pass of the whole hot path over every bucket of the workload:
-reduce-scatter (pack fused) of all buckets in gradient-ready order, fused SGD-momentum
-update of the owned shards, all-gather (unpack fused) in forward order -- one launch
-per bucket and phase, back to back on one stream, inputs resident in HBM.
+reduce-scatter (pack fused) of all buckets in gradient-ready order, SGD-momentum update of
+the owned shards, all-gather (unpack fused) in forward order -- by default one launch per
+bucket and phase, back to back on one stream, inputs resident in HBM.
 
 Prints ONE JSON line.  `value` is effective GB/s = algorithmic bytes / wall time, with
 algorithmic bytes per step N*(g*P + 4*P + 28): reduce-scatter reads g*P*N and writes 4N,
 the update reads 12N and writes 8N, the all-gather reads 4N and writes 4*P*N.
 
 Extra objects on the line:
+  step_ms       mean / median / min of the per-step durations (HIP events on the launch stream)
   roofline      the phase that takes the most time, its algorithmic bytes per launch over
                 its average launch duration (HIP events on the launch stream), against
-                the 8 TB/s HBM peak
-  cpu_baseline  the CPU oracle timed on this host on a bounded sample of the same
-                workload (a baseline, not a target); its output is also compared with
-                the GPU's on that sample
+                the 8 TB/s HBM peak; `traffic` = HBM bytes per launch from the rocprofv3
+                counter runs recorded in profiles/hbm_traffic.json, or null when the kernel
+                sources have changed since those runs
+  fused_rs_update  the same steps with reduce-scatter and update of a bucket in one kernel
+  cpu_baseline  the CPU oracle as it stands, timed on this host on the same workload (one
+                iteration, all buckets unless --sample-buckets says fewer; a baseline, not a
+                target); its output is also compared bit for bit with the GPU's first iteration
+
+--launch: per_bucket (default, the DeAR launch granularity), all_buckets (one launch per
+phase), graph (the per-bucket launches recorded once into a HIP graph and replayed).
+--hbm-probe: instead of the benchmark, print the bare-pattern HBM ceilings (one JSON line
+per pattern, see include/dear_probe.h).
 """
 from __future__ import annotations
 
@@ -31,14 +40,34 @@ import torch
 import workloads as W
 
 HBM_PEAK_GBPS = 8000.0
-# HBM bytes per launch (average over the buckets) from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE runs of this benchmark, each scaled by what the counter reads for a plain
-# 1 GiB device copy (fetch x2.0000, write x1.0000); summaries in profiles/.
-MEASURED_TRAFFIC_BYTES = {
-    ("bert_large", "rs"): 612670396, ("bert_large", "update"): 611343011, ("bert_large", "ag"): 1106461643,
-    ("resnet50", "rs"): 184355646, ("resnet50", "update"): 102255704, ("resnet50", "ag"): 187511994,
-    ("bert_base", "rs"): 1070366899, ("bert_base", "update"): 314614881, ("bert_base", "ag"): 1073750463,
-}
+ROOT = os.path.dirname(os.path.abspath(__file__))
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+KERNEL_SOURCES = ["paper_2302_12445_amd/csrc/dear_hip.hip", "paper_2302_12445_amd/csrc/plan.cpp",
+                  "paper_2302_12445_amd/csrc/dear_internal.h", "include/dear.h"]
+
+
+def kernel_source_hash() -> str:
+    import hashlib
+    h = hashlib.sha256()
+    for rel in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, rel), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def recorded_traffic(workload: str, phase: str):
+    """HBM bytes per launch (average over the buckets) from the rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE runs of this benchmark, each scaled by what the counter reads for a plain 1 GiB
+    device copy; None if there is no record for this workload or it was taken with other
+    kernel sources than the ones in the tree."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            rec = json.load(f)
+    except (OSError, ValueError):
+        return None
+    if rec.get("kernel_source_sha256") != kernel_source_hash():
+        return None
+    return rec.get("bytes_per_launch", {}).get(workload, {}).get(phase)
 
 
 def parse_args():
@@ -47,8 +76,11 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="bert_large", choices=W.WORKLOAD_NAMES)
-    ap.add_argument("--launch", default="per_bucket", choices=["per_bucket", "all_buckets"],
-                    help="one launch per bucket and phase (the DeAR schedule) or one per phase")
+    ap.add_argument("--launch", default="per_bucket", choices=["per_bucket", "all_buckets", "graph"],
+                    help="one launch per bucket and phase (the DeAR schedule), one per phase, or the "
+                         "per-bucket launches replayed from a HIP graph")
+    ap.add_argument("--hbm-probe", action="store_true",
+                    help="print the bare-pattern HBM ceilings instead of running the benchmark")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (torch) so that a counter "
@@ -164,6 +196,20 @@ class CpuBaseline:
         }
 
 
+def run_hbm_probe():
+    from paper_2302_12445_amd import hbm_probe
+    torch.cuda.init()
+    for row in hbm_probe.sweep():
+        print(json.dumps(row), flush=True)
+
+
+def stats(xs):
+    xs = sorted(xs)
+    n = len(xs)
+    med = xs[n // 2] if n % 2 else 0.5 * (xs[n // 2 - 1] + xs[n // 2])
+    return {"mean": round(sum(xs) / n, 4), "median": round(med, 4), "min": round(xs[0], 4)}
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -173,6 +219,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU (there is no CPU path)", file=sys.stderr)
         sys.exit(2)
+    if args.hbm_probe:
+        run_hbm_probe()
+        return
 
     from paper_2302_12445_amd.emulation import EmulatedWorkers
 
@@ -182,7 +231,8 @@ def main():
     em = EmulatedWorkers(w.sizes, w.P, w.grad_dtype, w.threshold_bytes, device)
     fill_inputs(em, w, device)
     nb = em.plan.n_buckets
-    per_bucket = args.launch == "per_bucket"
+    mode = args.launch
+    per_bucket = mode != "all_buckets"
 
     baseline = None
     if not args.no_cpu_baseline:
@@ -197,32 +247,47 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.warmup):
-        em.iteration(w.lr, w.momentum, per_bucket=per_bucket)
-    torch.cuda.synchronize()
+    graph = em.capture_iteration(w.lr, w.momentum, per_bucket=True) if mode == "graph" else None
 
-    # timed region: K steps; phase boundaries marked with events on the launch stream
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        ev[k][0].record()
-        if per_bucket:
+    def step(marks=None):
+        """One pass of the path; marks = [e0, e1, e2, e3] events recorded at the phase boundaries
+        (only the modes whose phases follow each other on one stream have inner boundaries)."""
+        if marks:
+            marks[0].record()
+        if mode == "graph":
+            graph.replay()
+        elif mode == "per_bucket":
             for b in range(nb):
                 em.reduce_scatter(b)
-            ev[k][1].record()
+            if marks:
+                marks[1].record()
             for b in range(nb):
                 em.shard_update(b, w.lr, w.momentum)
-            ev[k][2].record()
+            if marks:
+                marks[2].record()
             for b in reversed(range(nb)):
                 em.all_gather(b)
         else:
             em.reduce_scatter(-1)
-            ev[k][1].record()
+            if marks:
+                marks[1].record()
             em.shard_update(-1, w.lr, w.momentum)
-            ev[k][2].record()
+            if marks:
+                marks[2].record()
             em.all_gather(-1)
-        ev[k][3].record()
+        if marks:
+            marks[3].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # timed region: K steps; step and phase boundaries marked with events on the launch stream
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(ev[k])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
@@ -249,34 +314,43 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     value = bytes_["total"] / (wall / args.steps) / 1e9
     launches = nb if per_bucket else 1
-    phase_ms = {}
-    for i, name in enumerate(("rs", "update", "ag")):
-        phase_ms[name] = sum(ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(args.steps)) / args.steps
-    kernel_of = {"rs": "reduce_scatter_kernel", "update": "shard_update_kernel", "ag": "all_gather_kernel"}
-    dom = max(phase_ms, key=phase_ms.get)
-    achieved = bytes_[dom] / (phase_ms[dom] * 1e-3) / 1e9
-    roofline = {
-        "bound": "hbm", "kernel": kernel_of[dom], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-        "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom)) if per_bucket else None,
-        "bytes_per_launch": bytes_[dom] // launches, "launches_per_step": launches,
-        "avg_launch_ms": round(phase_ms[dom] / launches, 4),
-        "phases": {n: {"ms": round(phase_ms[n], 4), "GBps": round(bytes_[n] / (phase_ms[n] * 1e-3) / 1e9, 1)}
-                   for n in phase_ms},
-    }
+    step_ms = [ev[k][0].elapsed_time(ev[k][3]) for k in range(args.steps)]
     line = {
         "metric": "effective aggregation GB/s (RS+update+AG)", "value": round(value, 1), "unit": "GB/s",
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "step_ms": stats(step_ms),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "f32" if w.grad_dtype == "f32" else "f32 (gradients stored as bf16, widened exactly)",
         "data": "synthetic",
         "config": {"workload": w.name, "P": w.P, "N": w.N, "n_layers": w.n_layers, "buckets": nb,
                    "threshold_bytes": w.threshold_bytes if w.threshold_bytes != W.NO_LIMIT else "no limit",
                    "grad_dtype": w.grad_dtype, "launch": args.launch,
                    "algorithmic_bytes_per_step": bytes_["total"]},
-        "roofline": roofline,
     }
+    if mode in ("per_bucket", "all_buckets"):
+        phase_ms = {}
+        for i, name in enumerate(("rs", "update", "ag")):
+            phase_ms[name] = sum(ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(args.steps)) / args.steps
+        kernel_of = {"rs": "reduce_scatter_kernel", "update": "shard_update_kernel", "ag": "all_gather_kernel"}
+        dom = max(phase_ms, key=phase_ms.get)
+        achieved = bytes_[dom] / (phase_ms[dom] * 1e-3) / 1e9
+        line["roofline"] = {
+            "bound": "hbm", "kernel": kernel_of[dom], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+            "traffic": recorded_traffic(w.name, dom) if mode == "per_bucket" else None,
+            "traffic_source": "profiles/hbm_traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, calibrated)",
+            "bytes_per_launch": bytes_[dom] // launches, "launches_per_step": launches,
+            "avg_launch_ms": round(phase_ms[dom] / launches, 4),
+            "phases": {n: {"ms": round(phase_ms[n], 4), "GBps": round(bytes_[n] / (phase_ms[n] * 1e-3) / 1e9, 1)}
+                       for n in phase_ms},
+        }
+    else:  # one graph launch: no inner event boundaries, price the whole step
+        med = stats(step_ms)["median"]
+        line["roofline"] = {"bound": "hbm", "kernel": "whole step (one graph replay)",
+                            "achieved": round(bytes_["total"] / (med * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS,
+                            "unit": "GB/s", "frac": round(bytes_["total"] / (med * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                            "traffic": None}
     f_rs = sum(fev[k][0].elapsed_time(fev[k][1]) for k in range(args.steps)) / args.steps
     f_ag = sum(fev[k][1].elapsed_time(fev[k][2]) for k in range(args.steps)) / args.steps
     fused_rs_bytes = bytes_["rs"] + bytes_["update"] - 8 * w.N   # gbar neither written nor re-read

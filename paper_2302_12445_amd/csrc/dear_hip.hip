@@ -52,7 +52,7 @@ struct dear_ctx_impl {
 // defaults are the fastest found).  *_U = 16-byte vectors per lane; a tile of
 // DEAR_TILE_ELEMS is shared by TILE_VECS / (U * DEAR_BLOCK) workgroups.
 #ifndef DEAR_RS_U_F32
-#define DEAR_RS_U_F32 4
+#define DEAR_RS_U_F32 1
 #endif
 #ifndef DEAR_RS_U_BF16
 #define DEAR_RS_U_BF16 2
@@ -76,7 +76,7 @@ struct dear_ctx_impl {
 #define DEAR_AG_NT_STORE 1
 #endif
 #ifndef DEAR_UPD_U
-#define DEAR_UPD_U 2
+#define DEAR_UPD_U 1
 #endif
 #ifndef DEAR_UPD_NT_LOAD
 #define DEAR_UPD_NT_LOAD 1
@@ -183,6 +183,17 @@ __device__ __forceinline__ void for_each_item(unsigned n_items, int prio, Body b
             __builtin_amdgcn_s_setprio(3);
         for (unsigned item = blockIdx.x; item < n_items; item += gridDim.x) body(item);
     }
+}
+
+// Orders LDS traffic among the lanes of ONE wavefront (each wavefront of the reduce-scatter
+// owns its own staging area, so no other wavefront is involved): the hardware performs a
+// wavefront's LDS operations in issue order, so all that is needed is that the compiler
+// keeps the stores before and the loads after this point.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 // Where a reduce-scatter result goes.  Plain: gbar is stored to the gradient shard buffer.
@@ -322,10 +333,10 @@ __device__ __forceinline__ void reduce_scatter_tile(const dear_tile &t, int part
             }
             *reinterpret_cast<f4 *>(sw + 8 * lane) = lo;
             *reinterpret_cast<f4 *>(sw + 8 * lane + 4) = hi;
-            __syncthreads();
+            wave_lds_sync();
             const f4 o0 = *reinterpret_cast<const f4 *>(sw + 4 * lane);
             const f4 o1 = *reinterpret_cast<const f4 *>(sw + 256 + 4 * lane);
-            __syncthreads();
+            wave_lds_sync();
             emit_piece<FUSED>(o, piece_idx[u][0], o0, w_old[u][0], v_old[u][0]);
             emit_piece<FUSED>(o, piece_idx[u][PIECES - 1], o1, w_old[u][PIECES - 1], v_old[u][PIECES - 1]);
         }
