@@ -19,11 +19,25 @@ This module is stream/event plumbing: every aggregation step runs in the library
 from __future__ import annotations
 
 import time
-from typing import Callable, Dict, List, Optional
+from typing import Callable, Dict, List, Optional, Sequence, Union
 
 import torch
 
 from .emulation import EmulatedWorkers
+
+
+def spread_gemms(total: int, plan) -> List[int]:
+    """Split `total` GEMMs of synthetic compute over the plan's buckets in proportion to the
+    number of layers each bucket holds, with the remainders carried along, so that the sum is
+    `total` for every plan: the model's compute does not change when its gradients are
+    grouped differently (a bucket with few layers may get none)."""
+    out, seen = [], 0
+    L = plan.n_layers
+    for b in range(plan.n_buckets):
+        lo = total * seen // L
+        seen += plan.bucket_n_layers[b]
+        out.append(total * seen // L - lo)
+    return out
 
 
 def streams_run_concurrently(busy: torch.cuda.Stream, other: torch.cuda.Stream, work: Callable[[], None],
@@ -51,7 +65,7 @@ class DearSchedule:
     MODES = ("dear", "wfbp", "serial", "compute_only", "comm_only")
 
     def __init__(self, em: EmulatedWorkers, lr: float, momentum: float, gemm_dim: int = 4096,
-                 ff_gemms: int = 1, bp_gemms: int = 2,
+                 ff_gemms: Union[int, Sequence[int]] = 1, bp_gemms: Union[int, Sequence[int]] = 2,
                  on_backward: Optional[Callable[[int, int], None]] = None,
                  overlap_workgroups: int = 256, overlap_workgroups_ag: Optional[int] = 256,
                  fused_update: bool = True, gemm_dtype: torch.dtype = torch.float32,
@@ -84,7 +98,11 @@ class DearSchedule:
         if overlap_workgroups == 0:
             self.overlap_workgroups_ag = 0
         self.nb = em.plan.n_buckets
-        self.ff_gemms, self.bp_gemms = ff_gemms, bp_gemms
+        # GEMMs per bucket: one number for every bucket, or one per bucket (backward order)
+        self.ff_gemms = [ff_gemms] * self.nb if isinstance(ff_gemms, int) else list(ff_gemms)
+        self.bp_gemms = [bp_gemms] * self.nb if isinstance(bp_gemms, int) else list(bp_gemms)
+        if len(self.ff_gemms) != self.nb or len(self.bp_gemms) != self.nb:
+            raise ValueError("one GEMM count per bucket expected")
         self.on_backward = on_backward
         dev = em.device
         self.a = torch.randn(gemm_dim, gemm_dim, device=dev, dtype=torch.float32).to(gemm_dtype)
@@ -124,7 +142,7 @@ class DearSchedule:
             for b in reversed(range(self.nb)):
                 if wait_for_ag and self._have_ag:
                     self.compute.wait_event(self.ag_done[b])      # FeedPipe: OP2 of b before FF of b
-                self._gemms(self.ff_gemms)
+                self._gemms(self.ff_gemms[b])
 
     def _backward(self, signal: bool) -> None:
         """Back-propagation compute, last layer (bucket 0) to first."""
@@ -134,7 +152,7 @@ class DearSchedule:
                     # the tensors of bucket b are still read by the previous iteration's OP1
                     # until rs_done[b]; in order on the communication stream this is long past
                     self.compute.wait_event(self.rs_done[b])
-                self._gemms(self.bp_gemms)
+                self._gemms(self.bp_gemms[b])
                 if self.on_backward is not None:
                     self.on_backward(self.iteration_index, b)
                 if signal:

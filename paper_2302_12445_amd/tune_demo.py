@@ -21,7 +21,7 @@ if ROOT not in sys.path:
 def main() -> None:
     import workloads as W
     from paper_2302_12445_amd.emulation import EmulatedWorkers
-    from paper_2302_12445_amd.schedule import DearSchedule
+    from paper_2302_12445_amd.schedule import DearSchedule, spread_gemms
     from paper_2302_12445_amd.tuner import MB, BufferSizeTuner, grid_search, random_search
 
     ap = argparse.ArgumentParser()
@@ -29,8 +29,8 @@ def main() -> None:
     ap.add_argument("--trials", type=int, default=12)
     ap.add_argument("--steps", type=int, default=10, help="iterations averaged per trial")
     ap.add_argument("--gemm-dim", type=int, default=2048)
-    ap.add_argument("--layers-per-gemm", type=int, default=8,
-                    help="one forward (two backward) GEMMs per this many parameter tensors")
+    ap.add_argument("--forward-gemms", type=int, default=20,
+                    help="GEMMs of the whole forward pass (twice as many backward), the same for every plan")
     ap.add_argument("--baselines", action="store_true", help="also run random and grid search")
     args = ap.parse_args()
     if not torch.cuda.is_available():
@@ -50,12 +50,13 @@ def main() -> None:
 
     def measure(x_bytes: int) -> float:
         """Iterations per second of the DeAR schedule with buffer size x.  The synthetic
-        compute is spread over the layers, so a plan with more buckets has finer pipelining
-        but more launches -- the trade-off the paper tunes."""
+        compute is the same for every plan and is spread over the buckets by their layer
+        counts, so a plan with more buckets has finer pipelining but more launches -- the
+        trade-off the paper tunes."""
         em.replan(int(x_bytes))
-        nb = em.plan.n_buckets
-        per_bucket = max(1, round(w.n_layers / args.layers_per_gemm / nb))
-        sched = DearSchedule(em, w.lr, w.momentum, args.gemm_dim, ff_gemms=per_bucket, bp_gemms=2 * per_bucket)
+        sched = DearSchedule(em, w.lr, w.momentum, args.gemm_dim,
+                             ff_gemms=spread_gemms(args.forward_gemms, em.plan),
+                             bp_gemms=spread_gemms(2 * args.forward_gemms, em.plan))
         ms = sched.time_mode("dear", iterations=args.steps, warmup=2)
         n_trials[0] += 1
         return 1e3 / ms
