@@ -41,6 +41,8 @@ def main() -> None:
     ap.add_argument("--wave-priority-ag", type=int, default=0, help="wave priority of the bounded all-gather")
     ap.add_argument("--unfused", action="store_true", help="reduce-scatter and update as two kernels")
     ap.add_argument("--gemm-dtype", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--blas", default="default", choices=["default", "hipblaslt", "rocblas"],
+                    help="library torch takes its GEMM kernels from")
     ap.add_argument("--trace-iterations", type=int, default=0,
                     help="after the report, run this many DeAR iterations only (for a kernel trace)")
     args = ap.parse_args()
@@ -48,6 +50,8 @@ def main() -> None:
         print("schedule_demo needs a GPU", file=sys.stderr)
         sys.exit(2)
 
+    if args.blas != "default":
+        torch.backends.cuda.preferred_blas_library("cublaslt" if args.blas == "hipblaslt" else "cublas")
     device = "cuda:0"
     w = W.get_workload(args.workload)
     em = EmulatedWorkers(w.sizes, w.P, w.grad_dtype, w.threshold_bytes, device)
@@ -67,7 +71,7 @@ def main() -> None:
     rep = overlap_report(sched, args.iterations)
     rep["config"] = {"workload": w.name, "P": w.P, "buckets": em.plan.n_buckets, "gemm_dim": args.gemm_dim,
                      "ff_gemms_per_bucket": args.ff_gemms, "bp_gemms_per_bucket": args.bp_gemms,
-                     "gemm_dtype": args.gemm_dtype, "fused_update": not args.unfused,
+                     "gemm_dtype": args.gemm_dtype, "blas": args.blas, "fused_update": not args.unfused,
                      "overlap_workgroups": [args.overlap_workgroups, args.overlap_workgroups_ag],
                      "wave_priority": [args.wave_priority, args.wave_priority_ag]}
     print(json.dumps(rep), flush=True)
