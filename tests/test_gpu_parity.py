@@ -91,9 +91,10 @@ class Pair:
         oracle.shard_update(self.op, -1, self.sg, self.sp, self.sm, w.lr, w.momentum)
         oracle.all_gather(self.op, -1, self.sp, self.params)
 
-    def run(self, iterations=3, per_bucket=True, poison=True, stream=None, fused=False, width=0):
+    def run(self, iterations=3, per_bucket=True, poison=True, stream=None, fused=False, width=0, priority=0):
         w, em = self.w, self.em
         em.set_max_workgroups(width)
+        em.set_wave_priority(priority)
         self.seed_shards()
         for it in range(iterations):
             self.load_grads(it)
@@ -167,7 +168,7 @@ def test_bounded_grid_gives_the_same_bits(width, dtype):
     g = 4 if dtype == "f32" else 2
     w = small_workload(RAGGED + [300_001], 4, 40000 * g, dtype, index=120 + width)
     pr = Pair(w)
-    pr.run(2, per_bucket=(width != 3), fused=(width == 64), width=width)
+    pr.run(2, per_bucket=(width != 3), fused=(width == 64), width=width, priority=width % 4)
     pr.close()
 
 
@@ -371,5 +372,5 @@ def test_random_configurations():
         say("case: random %d sizes=%s P=%d %s thr=%d width=%d fused=%d per_bucket=%d %s" % (
             case, sizes, P, dtype, thr, width, fused, per_bucket, layout))
         pr = Pair(small_workload(sizes, P, thr, dtype, index=1000 + case), layout=layout)
-        pr.run(2, per_bucket=per_bucket, fused=fused, width=width)
+        pr.run(2, per_bucket=per_bucket, fused=fused, width=width, priority=case % 4)
         pr.close()

@@ -141,6 +141,15 @@ def test_all_gather_workers_range_errors_and_subset():
     sp = C.c_void_p(em.shard_param.data_ptr())
     for first, n in ((-1, 1), (0, 0), (0, 5), (3, 2), (4, 1)):
         assert lib.dear_all_gather_workers(em.ctx.handle, -1, sp, first, n, None) == binding.DEAR_ERANGE
+    for bad in (-1, 4):
+        assert lib.dear_ctx_set_wave_priority(em.ctx.handle, bad) == binding.DEAR_EINVAL
+    assert lib.dear_ctx_set_max_workgroups(em.ctx.handle, -1) == binding.DEAR_EINVAL
+    # a bound below the tile count but above nothing else: the bounded all-gather must still cover everything
+    em.set_max_workgroups(1)
+    em.shard_param.fill_(9.0)
+    dear.dear_all_gather(em.ctx, -1, em.shard_param.data_ptr())
+    torch.cuda.synchronize()
+    assert all(bool((t == 9.0).all()) for p in range(4) for t in em.params[p])
     em.close()
 
 

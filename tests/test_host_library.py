@@ -137,6 +137,8 @@ def test_calls_reject_bad_arguments_before_touching_the_gpu():
     assert lib.dear_shard_update(None, 0, None, None, None, 0.1, 0.9, None) == binding.DEAR_EINVAL
     assert lib.dear_all_gather(None, 0, None, None) == binding.DEAR_EINVAL
     assert lib.dear_scatter_params(None, 0, None, None) == binding.DEAR_EINVAL
+    assert lib.dear_ctx_set_max_workgroups(None, 4) == binding.DEAR_EINVAL
+    assert lib.dear_ctx_set_wave_priority(None, 1) == binding.DEAR_EINVAL
     pl = dear.dear_plan([8, 8], 2, 0, 4)
     out = C.c_void_p()
     good = (C.c_void_p * 4)(0x1000, 0x2000, 0x3000, 0x4000)
