@@ -18,6 +18,7 @@ Extra objects on the line:
                 counter runs recorded in profiles/hbm_traffic.json, or null when the kernel
                 sources have changed since those runs
   fused_rs_update  the same steps with reduce-scatter and update of a bucket in one kernel
+  fused_update_ag  the same steps with update and all-gather of a bucket in one kernel
   cpu_baseline  the CPU oracle as it stands, timed on this host on the same workload (one
                 iteration, all buckets unless --sample-buckets says fewer; a baseline, not a
                 target); its output is also compared bit for bit with the GPU's first iteration
@@ -361,6 +362,30 @@ def main():
         "moved_GBps": round((bytes_["total"] - 8 * w.N) / (fwall / args.steps) / 1e9, 1),
         "phases": {"rs_update": {"ms": round(f_rs, 4), "GBps": round(fused_rs_bytes / (f_rs * 1e-3) / 1e9, 1)},
                    "ag": {"ms": round(f_ag, 4), "GBps": round(bytes_["ag"] / (f_ag * 1e-3) / 1e9, 1)}},
+    }
+    # and with update and all-gather of a bucket in one kernel (moves 4N fewer bytes, but writes the
+    # replicas as P interleaved streams)
+    gev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    for _ in range(2):
+        em.iteration(w.lr, w.momentum, per_bucket=per_bucket, fused_gather=True)
+    torch.cuda.synchronize()
+    g0 = time.perf_counter()
+    for k in range(args.steps):
+        gev[k][0].record()
+        for b in buckets:
+            em.reduce_scatter(b)
+        gev[k][1].record()
+        for b in reversed(buckets):
+            em.update_all_gather(b, w.lr, w.momentum)
+        gev[k][2].record()
+    torch.cuda.synchronize()
+    gwall = time.perf_counter() - g0
+    g_ua = sum(gev[k][1].elapsed_time(gev[k][2]) for k in range(args.steps)) / args.steps
+    ua_bytes = bytes_["update"] + bytes_["ag"] - 4 * w.N
+    line["fused_update_ag"] = {
+        "note": "dear_reduce_scatter + dear_update_all_gather; moves 4N fewer bytes than the headline path",
+        "ms_per_step": round(gwall * 1e3 / args.steps, 4),
+        "phases": {"update_ag": {"ms": round(g_ua, 4), "GBps": round(ua_bytes / (g_ua * 1e-3) / 1e9, 1)}},
     }
     if baseline is not None:  # the CPU leg runs after every GPU timing
         line["cpu_baseline"] = baseline.run()

@@ -288,6 +288,22 @@ int dear_reduce_scatter_update(dear_ctx_t *ctx, int32_t bucket, float *shard_par
  */
 int dear_all_gather(dear_ctx_t *ctx, int32_t bucket, const float *shard_param, void *hip_stream);
 
+/* ---------------------------------------------------------------------------------
+ * dear_update_all_gather -- dear_shard_update and dear_all_gather of a bucket in one kernel:
+ * the updated parameter of a slot is stored to the shard buffer and to all P replicas' layer
+ * tensors while it is still in registers, so shard_param is not read again.  Same operations
+ * in the same order as the two separate calls: shard_param, shard_mom and every replica's
+ * parameters come out bit-identical.  It moves 4 bytes per element less than the two calls,
+ * but the update then runs where the all-gather runs (in the forward pass of the next
+ * iteration, paper Section III-B) and the replicas are written as P interleaved streams,
+ * which the memory system sustains less well than the replica-by-replica order of
+ * dear_all_gather; it is provided for comparison.
+ *   shard_grad   device, read;  shard_param, shard_mom  device, updated in place
+ * Errors: DEAR_EINVAL, DEAR_ERANGE, DEAR_EALIGN, DEAR_EHIP.
+ */
+int dear_update_all_gather(dear_ctx_t *ctx, int32_t bucket, const float *shard_grad, float *shard_param,
+                           float *shard_mom, float lr, float momentum, void *hip_stream);
+
 /* dear_all_gather_workers -- dear_all_gather restricted to the workers
  * first_worker .. first_worker+n_workers-1 (only their parameter tensors are written).
  * With one worker it turns any shard buffer (e.g. the momentum shards) back into that

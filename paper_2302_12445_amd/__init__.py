@@ -9,5 +9,5 @@ from .binding import (  # noqa: F401
     dear_all_gather, dear_all_gather_workers, dear_ctx_create, dear_ctx_set_max_workgroups, dear_ctx_set_wave_priority,
     dear_plan, dear_plan_fixed_layers, dear_plan_tiles,
     dear_reduce_scatter, dear_reduce_scatter_static, dear_reduce_scatter_update,
-    dear_scatter_params, dear_shard_update, dear_version, load_library, strerror,
+    dear_scatter_params, dear_shard_update, dear_update_all_gather, dear_version, load_library, strerror,
 )

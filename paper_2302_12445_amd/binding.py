@@ -24,7 +24,7 @@ EXPORTS = [
     "dear_plan", "dear_plan_fixed_layers", "dear_plan_free", "dear_plan_view", "dear_plan_tiles",
     "dear_ctx_create", "dear_ctx_destroy", "dear_ctx_set_max_workgroups", "dear_ctx_set_wave_priority",
     "dear_reduce_scatter", "dear_reduce_scatter_static", "dear_reduce_scatter_update", "dear_shard_update", "dear_all_gather",
-    "dear_all_gather_workers", "dear_scatter_params", "dear_strerror", "dear_version",
+    "dear_all_gather_workers", "dear_update_all_gather", "dear_scatter_params", "dear_strerror", "dear_version",
 ]
 
 
@@ -88,6 +88,7 @@ def load_library() -> C.CDLL:
     lib.dear_shard_update.argtypes = [vp, i32, vp, vp, vp, f32, f32, vp]
     lib.dear_reduce_scatter_update.argtypes = [vp, i32, vp, vp, f32, f32, vp]
     lib.dear_all_gather.argtypes = [vp, i32, vp, vp]
+    lib.dear_update_all_gather.argtypes = [vp, i32, vp, vp, vp, f32, f32, vp]
     lib.dear_all_gather_workers.argtypes = [vp, i32, vp, i32, i32, vp]
     lib.dear_scatter_params.argtypes = [vp, i32, vp, vp]
     lib.dear_strerror.argtypes = [C.c_int]
@@ -95,7 +96,7 @@ def load_library() -> C.CDLL:
     lib.dear_version.restype = C.c_int
     for name in ("dear_plan", "dear_plan_fixed_layers", "dear_plan_view", "dear_plan_tiles", "dear_ctx_create",
                  "dear_reduce_scatter", "dear_reduce_scatter_static", "dear_reduce_scatter_update", "dear_shard_update", "dear_all_gather",
-                 "dear_all_gather_workers", "dear_scatter_params"):
+                 "dear_all_gather_workers", "dear_update_all_gather", "dear_scatter_params"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -266,6 +267,13 @@ def dear_reduce_scatter_update(ctx: Context, bucket: int, shard_param: int, shar
 def dear_all_gather(ctx: Context, bucket: int, shard_param: int, stream: Optional[int] = None) -> None:
     _check(load_library().dear_all_gather(ctx.handle, bucket, C.c_void_p(shard_param), _stream(stream)),
            "dear_all_gather")
+
+
+def dear_update_all_gather(ctx: Context, bucket: int, shard_grad: int, shard_param: int, shard_mom: int,
+                           lr: float, momentum: float, stream: Optional[int] = None) -> None:
+    _check(load_library().dear_update_all_gather(ctx.handle, bucket, C.c_void_p(shard_grad),
+                                                 C.c_void_p(shard_param), C.c_void_p(shard_mom),
+                                                 lr, momentum, _stream(stream)), "dear_update_all_gather")
 
 
 def dear_all_gather_workers(ctx: Context, bucket: int, shard_param: int, first_worker: int, n_workers: int,

@@ -568,6 +568,96 @@ __global__ __launch_bounds__(DEAR_BLOCK) void all_gather_bounded_kernel(
     });
 }
 
+// Update and all-gather of a bucket in one kernel: a workgroup takes one tile, applies the
+// SGD-momentum update to the tile's slots (the same four separately rounded operations as
+// shard_update_kernel), stores the new w and v to the shard buffers and the new w to all
+// receiving replicas' layer tensors.  The updated value has to reach every replica from the
+// workgroup that computed it, so the stores go to all replicas at once (P interleaved write
+// streams) instead of replica by replica as in all_gather_kernel.
+template <bool ALL_FULL>
+__device__ __forceinline__ void update_gather_tile(const dear_tile &t, float *const *__restrict__ param_tab, int L,
+                                                   int P, const float *__restrict__ g, float *__restrict__ w,
+                                                   float *__restrict__ v, float lr, float mu)
+{
+    constexpr int VE = 4, U = DEAR_TILE_ELEMS / (VE * DEAR_BLOCK);
+    const int tid = threadIdx.x;
+    const int64_t a = t.src_begin, c = a + t.count;
+    const int64_t v_first = a / VE;
+    int64_t vi[U];
+    bool full[U];
+    f4 gg[U], ww[U], vv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        vi[u] = v_first + u * DEAR_BLOCK + tid;
+        const int64_t e0 = vi[u] * VE;
+        full[u] = ALL_FULL || (e0 >= a && e0 + VE <= c);
+        if (full[u]) {
+            const int64_t slot = t.dst_begin + (e0 - a);
+            gg[u] = load_f4_dword_aligned<DEAR_UPD_NT_LOAD>(g + slot);
+            ww[u] = load_f4_dword_aligned<DEAR_UPD_NT_LOAD>(w + slot);
+            vv[u] = load_f4_dword_aligned<DEAR_UPD_NT_LOAD>(v + slot);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t e0 = vi[u] * VE;
+        if (full[u]) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float wj = ww[u][j], vj = vv[u][j];
+                sgd_momentum(gg[u][j], wj, vj, lr, mu);
+                ww[u][j] = wj;
+                vv[u][j] = vj;
+            }
+            const int64_t slot = t.dst_begin + (e0 - a);
+            store_f4_dword_aligned<DEAR_UPD_NT_STORE>(v + slot, vv[u]);
+            store_f4_dword_aligned<DEAR_UPD_NT_STORE>(w + slot, ww[u]);
+        } else if (e0 < c) {  // edge vector of the run: element by element, all replicas
+            for (int j = 0; j < VE; ++j) {
+                const int64_t e = e0 + j;
+                if (e < a || e >= c) continue;
+                const int64_t slot = t.dst_begin + (e - a);
+                float wj = w[slot], vj = v[slot];
+                sgd_momentum(g[slot], wj, vj, lr, mu);
+                v[slot] = vj;
+                w[slot] = wj;
+                for (int q = 0; q < P; ++q)
+                    ((DEAR_GLOBAL float *)param_tab[(size_t)q * L + t.layer])[e] = wj;
+            }
+        }
+    }
+    for (int q = 0; q < P; ++q) {
+        DEAR_GLOBAL float *out = (DEAR_GLOBAL float *)param_tab[(size_t)q * L + t.layer];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (full[u]) store_vec<DEAR_AG_NT_STORE>((global_f4_out)out + vi[u], ww[u]);
+    }
+}
+
+template <bool BOUNDED>
+__global__ __launch_bounds__(DEAR_BLOCK) void update_all_gather_kernel(
+    const dear_tile *__restrict__ tiles, float *const *__restrict__ param_tab, int L, int P,
+    const float *__restrict__ g, float *__restrict__ w, float *__restrict__ v, float lr, float mu,
+    unsigned n_tiles, int prio)
+{
+    for_each_item<BOUNDED>(n_tiles, prio, [&](unsigned item) {
+        const dear_tile t = tiles[item];
+        if (t.layer < 0) {  // padding slots are updated like any other (their averaged gradient is +0)
+            for (int i = threadIdx.x; i < t.count; i += DEAR_BLOCK) {
+                const int64_t slot = t.dst_begin + i;
+                float wj = w[slot], vj = v[slot];
+                sgd_momentum(g[slot], wj, vj, lr, mu);
+                v[slot] = vj;
+                w[slot] = wj;
+            }
+        } else if (t.count == DEAR_TILE_ELEMS) {
+            update_gather_tile<true>(t, param_tab, L, P, g, w, v, lr, mu);
+        } else {
+            update_gather_tile<false>(t, param_tab, L, P, g, w, v, lr, mu);
+        }
+    });
+}
+
 // Inverse of the all-gather for one worker: layer tensors -> owned shard slots.
 __global__ __launch_bounds__(DEAR_BLOCK) void scatter_params_kernel(
     const dear_tile *__restrict__ tiles, float *const *__restrict__ param_tab, int L, int worker,
@@ -827,6 +917,32 @@ extern "C" int dear_shard_update(dear_ctx_t *c, int32_t bucket, const float *sha
         shard_update_kernel<UPD_U, false><<<dim3(static_cast<unsigned>(n_items)), dim3(DEAR_BLOCK), 0, st>>>(
             shard_grad, shard_param, shard_mom, c->row_len, base, vecs, lr, momentum,
             static_cast<unsigned>(blocks), static_cast<unsigned>(n_items), 0);
+    return launch_status();
+}
+
+extern "C" int dear_update_all_gather(dear_ctx_t *c, int32_t bucket, const float *shard_grad,
+                                      float *shard_param, float *shard_mom, float lr, float momentum,
+                                      void *hip_stream)
+{
+    int rc = check_call(c, bucket);
+    if (rc == DEAR_OK) rc = check_shard_buffer(shard_grad);
+    if (rc == DEAR_OK) rc = check_shard_buffer(shard_param);
+    if (rc == DEAR_OK) rc = check_shard_buffer(shard_mom);
+    if (rc != DEAR_OK) return rc;
+    if (shard_grad == shard_param || shard_grad == shard_mom || shard_param == shard_mom) return DEAR_EINVAL;
+    int64_t first, count;
+    tile_range(c, bucket, first, count);
+    if (count == 0) return DEAR_OK;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const unsigned width = grid_width(c->max_workgroups, count);
+    if (width < count)
+        update_all_gather_kernel<true><<<dim3(width), dim3(DEAR_BLOCK), 0, st>>>(
+            c->d_tiles + first, c->d_param, c->L, c->P, shard_grad, shard_param, shard_mom, lr, momentum,
+            static_cast<unsigned>(count), c->wave_priority);
+    else
+        update_all_gather_kernel<false><<<dim3(width), dim3(DEAR_BLOCK), 0, st>>>(
+            c->d_tiles + first, c->d_param, c->L, c->P, shard_grad, shard_param, shard_mom, lr, momentum,
+            static_cast<unsigned>(count), 0);
     return launch_status();
 }
 

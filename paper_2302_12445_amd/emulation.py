@@ -102,12 +102,23 @@ class EmulatedWorkers:
     def all_gather(self, bucket: int = -1, stream=None) -> None:
         B.dear_all_gather(self.ctx, bucket, self.shard_param.data_ptr(), _stream_handle(stream))
 
+    def update_all_gather(self, bucket: int, lr: float, momentum: float, stream=None) -> None:
+        B.dear_update_all_gather(self.ctx, bucket, self.shard_grad.data_ptr(), self.shard_param.data_ptr(),
+                                 self.shard_mom.data_ptr(), lr, momentum, _stream_handle(stream))
+
     def iteration(self, lr: float, momentum: float, per_bucket: bool = True, stream=None,
-                  fused_update: bool = False) -> None:
+                  fused_update: bool = False, fused_gather: bool = False) -> None:
         """One pass of the whole path on one stream: reduce-scatter the buckets in the order
         their gradients become ready, update the owned shards, all-gather in forward order.
-        fused_update: reduce-scatter and update of a bucket in one kernel."""
+        fused_update: reduce-scatter and update of a bucket in one kernel.
+        fused_gather: update and all-gather of a bucket in one kernel."""
         buckets = list(range(self.plan.n_buckets)) if per_bucket else [-1]
+        if fused_gather:
+            for b in buckets:
+                self.reduce_scatter(b, stream)
+            for b in reversed(buckets):
+                self.update_all_gather(b, lr, momentum, stream)
+            return
         if fused_update:
             for b in buckets:
                 self.reduce_scatter_update(b, lr, momentum, stream)

@@ -91,7 +91,8 @@ class Pair:
         oracle.shard_update(self.op, -1, self.sg, self.sp, self.sm, w.lr, w.momentum)
         oracle.all_gather(self.op, -1, self.sp, self.params)
 
-    def run(self, iterations=3, per_bucket=True, poison=True, stream=None, fused=False, width=0, priority=0):
+    def run(self, iterations=3, per_bucket=True, poison=True, stream=None, fused=False, width=0, priority=0,
+            fused_gather=False):
         w, em = self.w, self.em
         em.set_max_workgroups(width)
         em.set_wave_priority(priority)
@@ -104,7 +105,8 @@ class Pair:
                     for t in em.params[p]:
                         t.fill_(float("nan"))
             torch.cuda.synchronize()
-            em.iteration(w.lr, w.momentum, per_bucket=per_bucket, stream=stream, fused_update=fused)
+            em.iteration(w.lr, w.momentum, per_bucket=per_bucket, stream=stream, fused_update=fused,
+                         fused_gather=fused_gather)
             torch.cuda.synchronize()
             self.oracle_iteration()
             if not fused:  # the fused kernel never writes the averaged gradient
@@ -238,6 +240,20 @@ def test_fixed_layers_plan_resnet50_shape():
     assert plan.n_buckets == op.n_buckets == 41
     pr = Pair(w, plan=plan, oracle_plan=op)
     pr.run(1)
+    pr.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("P,width", [(1, 0), (4, 0), (8, 5), (13, 0)])
+def test_fused_update_all_gather_gives_the_same_bits(P, width, dtype):
+    """dear_update_all_gather: update and all-gather of a bucket in one kernel; shard buffers
+    (padding slots included) and every replica's parameters as from the two separate calls."""
+    say("case: fused update+all-gather P=%d width=%d %s" % (P, width, dtype))
+    g = 4 if dtype == "f32" else 2
+    w = small_workload(RAGGED + [100_003], P, 30000 * g, dtype, index=140 + P)
+    pr = Pair(w)
+    pr.run(3, fused_gather=True, width=width, priority=P % 4)
+    pr.run(1, per_bucket=False, fused_gather=True)
     pr.close()
 
 
