@@ -7,6 +7,7 @@
 #include <vector>
 
 #include "dear.h"
+#include "dear_internal.h"  // dear_emit_tiles, the emitter behind the tile table and the allocation-free entry point
 
 #define CHECK(c)                                                         \
     do {                                                                 \
@@ -70,6 +71,30 @@ static void one_case(std::mt19937_64 &rng)
     }
     CHECK(covered_elems == N);
     for (uint8_t s : slot) CHECK(s == 1);
+
+    // a capacity below the tile count: exactly that many entries are written, the count is still the full one
+    {
+        const int64_t cap = n_tiles / 2;
+        std::vector<dear_tile_t> part(static_cast<size_t>(cap));
+        int64_t n2 = -1;
+        CHECK(dear_plan_tiles(pl, part.data(), cap, &n2, nullptr) == DEAR_OK && n2 == n_tiles);
+        for (int64_t i = 0; i < cap; ++i) CHECK(part[i].dst_begin == tiles[i].dst_begin && part[i].count == tiles[i].count);
+    }
+    // the emitter on a range of buckets, into an exactly sized array, equals that range of the full table
+    {
+        const int b0 = static_cast<int>(rng() % v.n_buckets), b1 = b0 + 1 + static_cast<int>(rng() % (v.n_buckets - b0));
+        const int64_t want = begin[b1] - begin[b0];
+        std::vector<dear_tile_t> range(static_cast<size_t>(want));
+        std::vector<int64_t> rb(static_cast<size_t>(b1 - b0) + 1);
+        CHECK(dear_emit_tiles(*pl, b0, b1, range.data(), want, rb.data()) == want);
+        for (int64_t i = 0; i < want; ++i) {
+            const dear_tile_t &x = range[i], &y = tiles[begin[b0] + i];
+            CHECK(x.src_begin == y.src_begin && x.dst_begin == y.dst_begin && x.count == y.count &&
+                  x.layer == y.layer && x.shard == y.shard && x.bucket == y.bucket);
+        }
+        for (int b = b0; b <= b1; ++b) CHECK(rb[b - b0] == begin[b] - begin[b0]);
+        CHECK(dear_emit_tiles(*pl, b0, b1, nullptr, 0, nullptr) == want);
+    }
     dear_plan_free(pl);
 }
 
