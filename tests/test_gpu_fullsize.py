@@ -46,13 +46,15 @@ def _check_replicas_and_pads(em, op, w):
         assert bool((flat.view(torch.int32) == 0).all())
 
 
-@pytest.mark.parametrize("name,n_buckets,sample", [
-    ("bert_large", 11, [0, 5, 10]),   # P = 8, bf16 gradients, 64 MB; bucket 10 = word embedding alone
-    ("bert_base", 7, [0, 3, 6]),      # P = 16, fp32 gradients, 64 MB; bucket 6 = the oversized embedding
+@pytest.mark.parametrize("name,n_buckets,sample,per_bucket", [
+    ("bert_large", 11, [0, 5, 10], True),   # P = 8, bf16 gradients, 64 MB; bucket 10 = word embedding alone
+    ("bert_base", 7, [0, 3, 6], True),      # P = 16, fp32 gradients, 64 MB; bucket 6 = the oversized embedding
+    ("bert_large", 11, [1, 9], False),      # one launch per phase over all buckets (bench.py --launch all_buckets)
 ])
-def test_full_size_sampled_buckets(name, n_buckets, sample):
+def test_full_size_sampled_buckets(name, n_buckets, sample, per_bucket):
     from paper_2302_12445_amd.emulation import EmulatedWorkers
-    print("case: %s full size, buckets %s recomputed by the oracle" % (name, sample), flush=True)
+    print("case: %s full size, buckets %s recomputed by the oracle, %s" % (
+        name, sample, "one launch per bucket" if per_bucket else "one launch per phase"), flush=True)
     w = W.get_workload(name)
     em = EmulatedWorkers(w.sizes, w.P, w.grad_dtype, w.threshold_bytes, DEV)
     op = oracle.plan(w.sizes, w.P, w.threshold_bytes, w.grad_elem_bytes)
@@ -75,7 +77,7 @@ def test_full_size_sampled_buckets(name, n_buckets, sample):
         oracle.scatter_params(op, params, 0, sp, bucket=b)
 
     em.shard_grad.fill_(float("nan"))
-    em.iteration(w.lr, w.momentum, per_bucket=True)
+    em.iteration(w.lr, w.momentum, per_bucket=per_bucket)
     torch.cuda.synchronize()
 
     for b in sample:
