@@ -167,10 +167,11 @@ void dear_ctx_destroy(dear_ctx_t *ctx); /* NULL is ignored; synchronises the dev
 /* dear_ctx_set_max_workgroups -- bound the grid of the kernels launched through this
  * context.  0 (the default) gives every work item its own workgroup, which is fastest
  * when the aggregation has the GPU to itself.  A positive bound (a few hundred; 256 =
- * one per compute unit) makes each workgroup stride over the items; this is meant for the DeAR schedule on one GPU (paper Section III-B), where
- * the reduce-scatter runs beside back-propagation kernels and the all-gather beside
- * feed-forward kernels: a bounded grid disturbs the compute kernels far less.  Results
- * are identical for every setting.  Takes effect for calls made afterwards.
+ * one per compute unit) makes each workgroup stride over the items; this is meant for
+ * the DeAR schedule on one GPU (paper Section III-B), where the reduce-scatter runs
+ * beside back-propagation kernels and the all-gather beside feed-forward kernels: a
+ * bounded grid disturbs the compute kernels far less.  Results are identical for every
+ * setting.  Takes effect for calls made afterwards.
  * Errors: DEAR_EINVAL (null context, negative bound). */
 int dear_ctx_set_max_workgroups(dear_ctx_t *ctx, int32_t max_workgroups);
 

@@ -443,7 +443,8 @@ __global__ __launch_bounds__(DEAR_BLOCK) void shard_update_kernel(
 // (chunk, replica, part): the hardware starts workgroups in index order, so at any moment
 // the chip writes a long sequential run of one or two replicas instead of P interleaved
 // streams, which HBM sustains markedly better; the chunk's shard values
-// (DEAR_AG_CHUNK_BYTES, a few MiB) are re-read for replicas 1..P-1 from L2 / Infinity Cache, not HBM.
+// (DEAR_AG_CHUNK_BYTES: 16 MiB, i.e. 2 MiB in each XCD's 4 MiB L2, since a part is always read
+// by the same XCD) are re-read for replicas 1..P-1 from L2, not HBM.
 template <int U, bool ALL_FULL>
 __device__ __forceinline__ void all_gather_tile(const dear_tile &t, int part, DEAR_GLOBAL float *out,
                                                 const float *__restrict__ src)
