@@ -74,7 +74,7 @@ def recorded_traffic(workload: str, phase: str):
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="bert_large", choices=W.WORKLOAD_NAMES)
     ap.add_argument("--launch", default="per_bucket", choices=["per_bucket", "all_buckets", "graph"],
