@@ -216,3 +216,21 @@ def test_tiles_random():
 def test_tiles_resnet50():
     w = W.get_workload("resnet50")
     check_tiles(w.sizes, w.P, w.threshold_bytes, 4)
+
+
+def test_recorded_counter_traffic_belongs_to_the_kernel_sources_in_the_tree():
+    """bench.py reports roofline.traffic from profiles/hbm_traffic.json only while that record
+    was taken with the kernel sources in the tree; a change to them must be followed by new
+    counter runs (this test then fails until the record is renewed)."""
+    import json
+    import bench
+    rec = json.load(open(bench.TRAFFIC_FILE))
+    assert rec["kernel_source_sha256"] == bench.kernel_source_hash()
+    for wl in ("bert_large", "resnet50", "bert_base"):
+        w = W.get_workload(wl)
+        nb = oracle.plan(w.sizes, w.P, w.threshold_bytes, w.grad_elem_bytes).n_buckets
+        alg = w.algorithmic_bytes()
+        for phase in ("rs", "update", "ag"):
+            got = bench.recorded_traffic(wl, phase)
+            assert got is not None
+            assert 0.95 < got / (alg[phase] / nb) < 1.10, (wl, phase)   # HBM traffic ~ algorithmic bytes
